@@ -1,0 +1,110 @@
+/*
+ * s2a.h -- C ABI of the MI355X (gfx950) 4-bit GELU activation library.
+ *
+ * The library implements the non-parametric activation step of S2A
+ * (Sec. 3.2 "Non-Parametric Layers", Fig. 3, and the "GeLU layer" paragraph,
+ * Eq. 8-12): the forward pass evaluates the sigmoid-form GELU at full
+ * precision and keeps only a 4-bit code of the clipped input; the backward
+ * pass turns each code back into the derivative the paper fits for it and
+ * multiplies by the incoming gradient.
+ *
+ * Conventions shared by every entry point
+ *   - Returns an int: S2A_OK (0) or a negative S2A_ERR_* value.  Nothing
+ *     throws, nothing blocks: kernels are enqueued on `stream` and the call
+ *     returns.  Argument errors are detected on the host before any device
+ *     work, in the order NOT_INIT, DTYPE, SIZE, NULL.
+ *   - x, y, dy, dx and codes are DEVICE pointers owned by the caller.  The
+ *     library allocates no device memory and keeps no reference to them.
+ *   - Tensors are flat and contiguous; only the element count n matters.
+ *   - `dtype` is an s2a_dtype: the storage type of x/y/dy/dx.  Arithmetic is
+ *     fp32 for both; results are rounded once (nearest-even) to the storage
+ *     type.
+ *   - `codes` holds ceil(n/2) bytes: element 2j in bits 0..3 and element 2j+1
+ *     in bits 4..7 of byte j.  For odd n the last high nibble is written as 0.
+ *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *   - Pointers need only element alignment.  16-byte aligned x/y/dy/dx with
+ *     4-byte aligned codes take the vector kernels; anything else takes a
+ *     slower element-wise kernel with identical results.
+ *   - Exact aliasing y == x and dx == dy (in place) is allowed; any other
+ *     overlap between an input and an output is undefined.
+ */
+#ifndef S2A_H
+#define S2A_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { S2A_F32 = 0, S2A_BF16 = 1 } s2a_dtype;
+
+enum {
+    S2A_OK = 0,
+    S2A_ERR_NULL = -1,     /* a required pointer is NULL while n > 0 */
+    S2A_ERR_SIZE = -2,     /* n < 0 */
+    S2A_ERR_DTYPE = -3,    /* dtype is not an s2a_dtype */
+    S2A_ERR_LEVELS = -4,   /* s2a_qtable_init: levels != 16 */
+    S2A_ERR_NOT_INIT = -5, /* s2a_qtable_init has not succeeded yet */
+    S2A_ERR_LAUNCH = -6    /* the HIP runtime refused the launch */
+};
+
+/*
+ * Quantization-table setup (GeLU paragraph: x is clipped to [-2, 2] and
+ * quantized as in Eq. 8 with N = 4; backward dequantizes by Eq. 9 and applies
+ * Eq. 12).  Because a code takes only 2^N values, Eq. 9 followed by Eq. 12 is
+ * a 16-entry table: representatives xhat_k = -2 + k*4/15 and derivatives
+ * D[k] = sigma(1.702 xhat_k) + 0.22 sin(1.5 xhat_k).  The table is computed on
+ * the host in double precision, rounded once to fp32, and kept in process
+ * memory; kernels receive it by value, so there is no per-device state.
+ *
+ *   levels  number of quantization levels 2^N.  Only 16 is supported (two
+ *           codes per byte); anything else returns S2A_ERR_LEVELS and leaves
+ *           the library state unchanged.
+ *
+ * Idempotent.  Must not race with s2a_act_fwd / s2a_act_bwd on other threads.
+ */
+int s2a_qtable_init(int levels);
+
+/*
+ * Read back the table built by s2a_qtable_init (HOST pointers, any may be
+ * NULL): the 16 representatives (Eq. 9), the 16 derivatives (Eq. 12 at the
+ * representatives) and the 15 decision points half-way between neighbouring
+ * representatives.  Returns S2A_ERR_NOT_INIT before a successful init.
+ */
+int s2a_qtable_get(float xhat[16], float deriv[16], float bounds[15]);
+
+/*
+ * Forward pass (Fig. 3 forward; Eq. 10; clip + Eq. 8 applied to x):
+ *   y[i]    = x[i] * sigma(1.702 x[i])
+ *   code[i] = round_half_even((clip(x[i], -2, 2) + 2) * 15/4)   in 0..15
+ * x is read once; y and the packed codes are the only outputs, and the codes
+ * are all the backward pass needs.  NaN inputs give y = NaN and code 0;
+ * +inf gives y = +inf, code 15; -inf gives y = NaN, code 0.
+ *
+ *   x      [in]  device, n elements of `dtype`
+ *   y      [out] device, n elements of `dtype` (may equal x)
+ *   codes  [out] device, ceil(n/2) bytes
+ *   n      element count, >= 0; n == 0 returns S2A_OK without a launch
+ */
+int s2a_act_fwd(const void* x, void* y, uint8_t* codes, int64_t n, int dtype, void* stream);
+
+/*
+ * Backward pass (Fig. 3 backward; Eq. 9 then Eq. 12, then the chain rule):
+ *   dx[i] = dy[i] * D[code[i]]
+ *
+ *   dy     [in]  device, n elements of `dtype`
+ *   codes  [in]  device, ceil(n/2) bytes as written by s2a_act_fwd
+ *   dx     [out] device, n elements of `dtype` (may equal dy)
+ */
+int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int dtype,
+                void* stream);
+
+/* Static, NUL-terminated description of a return code.  Never NULL. */
+const char* s2a_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* S2A_H */

@@ -1,0 +1,131 @@
+"""CPU oracle for the S2A 4-bit GELU activation step -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes loader around ``s2a_oracle.c`` (plain C, IEEE double, scalar
+loops; S2A paper Sec. 3.2, GeLU paragraph, Eq. 8-12).  Only the tests, the
+smoke check and the benchmark's ``cpu_baseline`` leg may import this package;
+the GPU library and its Python binding never do, and nothing here imports
+them.  All arithmetic of the method lives in the C file; this module only
+marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+F32 = 0
+BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "s2a_oracle.c")
+_LIB = os.path.join(_HERE, "libs2a_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no vectorisation hints)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.run(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math",
+             "-ffp-contract=off", "-o", tmp, _SRC, "-lm"],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        d, i, i64, vp = ctypes.c_double, ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
+        for name in ("s2a_oracle_gelu", "s2a_oracle_gelu_deriv_exact",
+                     "s2a_oracle_gelu_deriv_approx"):
+            getattr(lib, name).restype = d
+            getattr(lib, name).argtypes = [d]
+        lib.s2a_oracle_quantize.restype = i
+        lib.s2a_oracle_quantize.argtypes = [d]
+        lib.s2a_oracle_dequantize.restype = d
+        lib.s2a_oracle_dequantize.argtypes = [i]
+        lib.s2a_oracle_table.restype = None
+        lib.s2a_oracle_table.argtypes = [vp, vp, vp]
+        lib.s2a_oracle_fwd.restype = i
+        lib.s2a_oracle_fwd.argtypes = [vp, i, i64, vp, vp, vp, vp, d]
+        lib.s2a_oracle_bwd.restype = i
+        lib.s2a_oracle_bwd.argtypes = [vp, i, vp, i64, vp]
+        _lib = lib
+    return _lib
+
+
+def gelu(x: float) -> float:
+    """Eq. 10 at one point."""
+    return _load().s2a_oracle_gelu(float(x))
+
+
+def gelu_deriv_exact(x: float) -> float:
+    """Eq. 11 at one point (cross-checks only)."""
+    return _load().s2a_oracle_gelu_deriv_exact(float(x))
+
+
+def gelu_deriv_approx(x: float) -> float:
+    """Eq. 12 at one point."""
+    return _load().s2a_oracle_gelu_deriv_approx(float(x))
+
+
+def quantize(x: float) -> int:
+    """Clip to [-2, 2] then Eq. 8 on x with N = 4."""
+    return _load().s2a_oracle_quantize(float(x))
+
+
+def dequantize(q: int) -> float:
+    """Eq. 9 on a code."""
+    return _load().s2a_oracle_dequantize(int(q))
+
+
+def table():
+    """(xhat[16], deriv[16], bounds[15]) as float64 arrays."""
+    xhat = np.empty(16, np.float64)
+    deriv = np.empty(16, np.float64)
+    bounds = np.empty(15, np.float64)
+    _load().s2a_oracle_table(xhat.ctypes.data, deriv.ctypes.data, bounds.ctypes.data)
+    return xhat, deriv, bounds
+
+
+def _storage(a: np.ndarray, dtype: int) -> np.ndarray:
+    """Check that `a` is the raw storage for `dtype`: float32, or uint16 bf16 bit patterns."""
+    want = np.float32 if dtype == F32 else np.uint16
+    if a.dtype != want or a.ndim != 1 or not a.flags.c_contiguous:
+        raise TypeError(f"oracle input must be a contiguous 1-D {np.dtype(want)} array")
+    return a
+
+
+def fwd(x: np.ndarray, dtype: int, band: float = 1e-6):
+    """Forward pass.  Returns (y float64[n], code uint8[n], packed uint8[(n+1)//2], near uint8[n])."""
+    x = _storage(x, dtype)
+    n = x.shape[0]
+    y = np.empty(n, np.float64)
+    code = np.empty(n, np.uint8)
+    packed = np.empty((n + 1) // 2, np.uint8)
+    near = np.empty(n, np.uint8)
+    rc = _load().s2a_oracle_fwd(x.ctypes.data, dtype, n, y.ctypes.data, code.ctypes.data,
+                                packed.ctypes.data, near.ctypes.data, float(band))
+    if rc != 0:
+        raise ValueError("s2a_oracle_fwd rejected its arguments")
+    return y, code, packed, near
+
+
+def bwd(dy: np.ndarray, dtype: int, packed: np.ndarray) -> np.ndarray:
+    """Backward pass from packed codes.  Returns dx float64[n]."""
+    dy = _storage(dy, dtype)
+    n = dy.shape[0]
+    if packed.dtype != np.uint8 or packed.shape != ((n + 1) // 2,) or not packed.flags.c_contiguous:
+        raise TypeError("packed must be contiguous uint8 of length ceil(n/2)")
+    dx = np.empty(n, np.float64)
+    rc = _load().s2a_oracle_bwd(dy.ctypes.data, dtype, packed.ctypes.data, n, dx.ctypes.data)
+    if rc != 0:
+        raise ValueError("s2a_oracle_bwd rejected its arguments")
+    return dx

@@ -1,0 +1,172 @@
+/*
+ * s2a_oracle.c -- CPU oracle for the 4-bit GELU activation step of S2A.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, scalar, double-precision
+ * statement of what the activation path computes.  It exists so that tests,
+ * the smoke check and the cpu_baseline leg of the benchmark have something
+ * obviously correct to compare the GPU library against.  Product code never
+ * links, imports or calls it, and it shares no code, header, table or
+ * constant generator with the HIP sources.
+ *
+ * What it follows (S2A paper, Sec. 3.2 "Non-Parametric Layers"):
+ *   - the general scheme of Fig. 3: forward computes y from the full-precision
+ *     x and saves only a low-bit activation; backward dequantizes it, forms
+ *     dy/dx and multiplies by dL/dy;
+ *   - "GeLU layer" paragraph: Eq. 10 (forward), Eq. 11 (exact derivative, used
+ *     here for cross-checks only), Eq. 12 (sine-fitted derivative used in the
+ *     backward pass), the clip of x to [-2, 2], and the statement that x is
+ *     quantized as in Eq. 8 and dequantized by Eq. 9 with N = 4 bits.
+ *
+ * Readings taken where the paper is silent (each is listed in the design
+ * notes of the repository):
+ *   - Eq. 8's min/max are the clip limits -2 and 2 (fixed, not measured from
+ *     the tensor): after the clip they are the extremes of any tensor that has
+ *     one element beyond each limit, and the activation interface carries no
+ *     per-tensor scale.
+ *   - The rounding function of Eq. 8 is round-half-to-even.
+ *   - NaN clips like C's fmax/fmin (the non-NaN operand wins), so NaN -> code 0.
+ *   - Two codes per byte, element 2j in bits 0..3 and element 2j+1 in bits
+ *     4..7 of byte j; an odd n leaves the last high nibble 0.  The paper only
+ *     says a code needs N bits; the packing order is this build's.
+ *
+ * Parity pins (tests/test_oracle_pins.py), none of which re-type a formula
+ * below: Eq. 10 against a library logistic function and the identity
+ * y(x) - y(-x) = x; Eq. 11 against automatic differentiation of Eq. 10;
+ * Eq. 12 at the points where the sine term is 0 or +-0.22 and the odd
+ * symmetry D(x) + D(-x) = 1; the quantizer against exact rational arithmetic
+ * over every bf16 bit pattern plus its invariants (monotone, 16 levels,
+ * representatives reproduce themselves, mirror symmetry); packing against a
+ * little-endian bit stream.  No function here is "parity unpinned".
+ *
+ * Everything is IEEE double unless a storage type is named.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+/* Quantizer constants: N = 4 bits (GeLU paragraph), range = the clip limits. */
+#define ORACLE_NBITS 4
+#define ORACLE_XMIN (-2.0)
+#define ORACLE_XMAX (2.0)
+
+static double logistic(double z) { return 1.0 / (1.0 + exp(-z)); }
+
+/* Eq. 10: y = x * sigma(1.702 x). */
+double s2a_oracle_gelu(double x) { return x * logistic(1.702 * x); }
+
+/* Eq. 11: sigma(1.702x) + 1.702 x e^{-1.702x} sigma^2(1.702x). Cross-check only. */
+double s2a_oracle_gelu_deriv_exact(double x)
+{
+    double z = 1.702 * x;
+    double s = logistic(z);
+    return s + z * exp(-z) * s * s;
+}
+
+/* Eq. 12: sigma(1.702x) + 0.22 sin(1.5x). */
+double s2a_oracle_gelu_deriv_approx(double x)
+{
+    return logistic(1.702 * x) + 0.22 * sin(1.5 * x);
+}
+
+/* Scale of Eq. 8 with max = 2, min = -2, N = 4. */
+static double quant_scale(void)
+{
+    return (ORACLE_XMAX - ORACLE_XMIN) / (double)((1 << ORACLE_NBITS) - 1);
+}
+
+/* Clip to [-2, 2] (GeLU paragraph), then Eq. 8 applied to x. */
+int s2a_oracle_quantize(double x)
+{
+    double xc = fmin(fmax(x, ORACLE_XMIN), ORACLE_XMAX);
+    double q = nearbyint((xc - ORACLE_XMIN) / quant_scale()); /* half-to-even */
+    return (int)q;
+}
+
+/* Eq. 9 applied to x_q. */
+double s2a_oracle_dequantize(int q) { return (double)q * quant_scale() + ORACLE_XMIN; }
+
+/*
+ * The 16 representatives xhat_k (Eq. 9), the derivative the backward pass
+ * uses for each (Eq. 12 at xhat_k), and the 15 decision points between
+ * neighbouring representatives.
+ */
+void s2a_oracle_table(double xhat[16], double deriv[16], double bounds[15])
+{
+    for (int k = 0; k < 16; ++k) {
+        xhat[k] = s2a_oracle_dequantize(k);
+        deriv[k] = s2a_oracle_gelu_deriv_approx(xhat[k]);
+    }
+    for (int j = 0; j < 15; ++j)
+        bounds[j] = ORACLE_XMIN + ((double)j + 0.5) * quant_scale();
+}
+
+/* Storage element i -> the exact double it denotes. */
+static double load_elem(const void *p, int dtype, int64_t i)
+{
+    if (dtype == ORACLE_F32) {
+        float f;
+        memcpy(&f, (const char *)p + 4 * i, 4);
+        return (double)f;
+    }
+    uint16_t h;
+    memcpy(&h, (const char *)p + 2 * i, 2);
+    uint32_t w = (uint32_t)h << 16; /* bf16 is the top half of an fp32 */
+    float f;
+    memcpy(&f, &w, 4);
+    return (double)f;
+}
+
+/* Distance from x to the nearest of the 15 decision points. */
+static double boundary_distance(double x)
+{
+    double best = INFINITY;
+    for (int j = 0; j < 15; ++j) {
+        double b = ORACLE_XMIN + ((double)j + 0.5) * quant_scale();
+        double d = fabs(x - b);
+        if (d < best) best = d;
+    }
+    return best;
+}
+
+/*
+ * Forward pass over n elements of x (storage type `dtype`).
+ *   y      [n]          Eq. 10 of each element, double           (may be NULL)
+ *   code   [n]          unpacked 4-bit codes, one per byte       (may be NULL)
+ *   packed [(n+1)/2]    two codes per byte, low nibble first     (may be NULL)
+ *   near   [n]          1 where x lies within `band` of a decision point of
+ *                       the quantizer, else 0                    (may be NULL)
+ * Returns 0, or -1 for a bad dtype / negative n.
+ */
+int s2a_oracle_fwd(const void *x, int dtype, int64_t n, double *y, uint8_t *code,
+                   uint8_t *packed, uint8_t *near, double band)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n < 0) return -1;
+    if (packed) memset(packed, 0, (size_t)((n + 1) / 2));
+    for (int64_t i = 0; i < n; ++i) {
+        double xi = load_elem(x, dtype, i);
+        int q = s2a_oracle_quantize(xi);
+        if (y) y[i] = s2a_oracle_gelu(xi);
+        if (code) code[i] = (uint8_t)q;
+        if (packed) packed[i / 2] |= (uint8_t)(q << (4 * (i & 1)));
+        if (near) near[i] = (uint8_t)(boundary_distance(xi) <= band);
+    }
+    return 0;
+}
+
+/*
+ * Backward pass: dx[i] = dy[i] * Eq.12(Eq.9(code[i])) with the codes read
+ * from the packed bytes (low nibble = even element).
+ */
+int s2a_oracle_bwd(const void *dy, int dtype, const uint8_t *packed, int64_t n, double *dx)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n < 0) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        int q = (packed[i / 2] >> (4 * (i & 1))) & 0xF;
+        double xhat = s2a_oracle_dequantize(q);
+        dx[i] = load_elem(dy, dtype, i) * s2a_oracle_gelu_deriv_approx(xhat);
+    }
+    return 0;
+}
