@@ -1,0 +1,94 @@
+"""ctypes binding of libs2a.so -- argument marshalling only.
+
+Function names and argument order follow include/s2a.h.  Device pointers are
+plain integers (e.g. ``tensor.data_ptr()``), the stream is a ``hipStream_t``
+as an integer (e.g. ``torch.cuda.current_stream().cuda_stream``).  Every step
+of the activation path runs inside the library's kernels; there is no Python
+or CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+F32 = 0
+BF16 = 1
+
+OK = 0
+ERR_NULL = -1
+ERR_SIZE = -2
+ERR_DTYPE = -3
+ERR_LEVELS = -4
+ERR_NOT_INIT = -5
+ERR_LAUNCH = -6
+
+EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd", "s2a_strerror")
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libs2a.so")
+_lib = None
+
+
+class S2AError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libs2a.so (built by ``python -m paper_2503_08154_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2503_08154_amd.build`; "
+                "there is no fallback path")
+        l = ctypes.CDLL(LIB_PATH)
+        vp, i, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        l.s2a_qtable_init.restype = i
+        l.s2a_qtable_init.argtypes = [i]
+        l.s2a_qtable_get.restype = i
+        l.s2a_qtable_get.argtypes = [vp, vp, vp]
+        l.s2a_act_fwd.restype = i
+        l.s2a_act_fwd.argtypes = [vp, vp, vp, i64, i, vp]
+        l.s2a_act_bwd.restype = i
+        l.s2a_act_bwd.argtypes = [vp, vp, vp, i64, i, vp]
+        l.s2a_strerror.restype = ctypes.c_char_p
+        l.s2a_strerror.argtypes = [i]
+        _lib = l
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().s2a_strerror(int(code)).decode()
+
+
+def qtable_init(levels: int = 16, check: bool = True) -> int:
+    rc = lib().s2a_qtable_init(int(levels))
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_qtable_init")
+    return rc
+
+
+def qtable_get():
+    """(xhat[16], deriv[16], bounds[15]) as Python lists of fp32 values."""
+    xh = (ctypes.c_float * 16)()
+    dv = (ctypes.c_float * 16)()
+    bd = (ctypes.c_float * 15)()
+    rc = lib().s2a_qtable_get(xh, dv, bd)
+    if rc != OK:
+        raise S2AError(rc, "s2a_qtable_get")
+    return list(xh), list(dv), list(bd)
+
+
+def act_fwd(x: int, y: int, codes: int, n: int, dtype: int, stream: int = 0, check: bool = True) -> int:
+    rc = lib().s2a_act_fwd(x, y, codes, int(n), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_act_fwd")
+    return rc
+
+
+def act_bwd(dy: int, codes: int, dx: int, n: int, dtype: int, stream: int = 0, check: bool = True) -> int:
+    rc = lib().s2a_act_bwd(dy, codes, dx, int(n), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_act_bwd")
+    return rc

@@ -1,0 +1,124 @@
+"""Comparison rules between the GPU library and the CPU oracle.
+
+Tolerances (stated by the benchmark spec, floors derived from the formats):
+  codes  bit-exact, except elements whose x lies within 1e-6 of a decision
+         point of the quantizer: those are counted, and if they differ they
+         must differ by exactly one level.
+  y      fp32: |err| <= 1e-6 * max(|y_ref|, FLT_MIN)   (below FLT_MIN fp32 has no
+               relative precision left, so the bound turns absolute there)
+         bf16: |err| <= 1 ulp, ulp = 2^(max(exponent(y_ref), -126) - 7)
+  dx     fp32: |err| <= 1e-5 * max(|dx_ref|, FLT_MIN);  bf16: <= 2 ulp
+Non-finite inputs are outside the tolerances: there only the kind of result
+(NaN / +inf / -inf) has to agree with the oracle.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+from paper_2503_08154_amd import workloads as wl
+
+FLT_MIN = float(np.finfo(np.float32).tiny)
+BAND = 1e-6
+
+
+def bf16_ulp(ref: np.ndarray) -> np.ndarray:
+    """Spacing of bf16 numbers in the binade of |ref| (denormal spacing below 2^-126)."""
+    a = np.abs(ref)
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.where(a > 0, e, -126.0)
+    e = np.clip(e, -126.0, 127.0)
+    return np.exp2(e - 7.0)
+
+
+def unpack(packed: np.ndarray, n: int) -> np.ndarray:
+    """uint8[(n+1)//2] -> uint8[n] codes, low nibble first."""
+    out = np.empty(2 * packed.shape[0], np.uint8)
+    out[0::2] = packed & 0x0F
+    out[1::2] = packed >> 4
+    return out[:n]
+
+
+@dataclass
+class CodeReport:
+    n: int
+    flagged: int      # elements inside the band
+    differing: int    # nibbles that differ from the oracle (all must be flagged)
+    pad_ok: bool
+
+    def __str__(self):
+        return f"codes: n={self.n} in-band={self.flagged} differing={self.differing}"
+
+
+def check_codes(packed_gpu: np.ndarray, code_ref: np.ndarray, near: np.ndarray, n: int) -> CodeReport:
+    assert packed_gpu.shape == ((n + 1) // 2,)
+    got = unpack(packed_gpu, n)
+    diff = got != code_ref
+    # every differing nibble is in the band and off by one level
+    bad = diff & (near == 0)
+    assert not bad.any(), (
+        f"{int(bad.sum())} codes differ outside the 1e-6 band, first at {int(np.argmax(bad))}: "
+        f"gpu={got[np.argmax(bad)]} oracle={code_ref[np.argmax(bad)]}")
+    if diff.any():
+        step = np.abs(got[diff].astype(np.int16) - code_ref[diff].astype(np.int16))
+        assert (step == 1).all(), "an in-band code differs by more than one level"
+    pad_ok = True
+    if n % 2:
+        pad_ok = (packed_gpu[-1] >> 4) == 0
+        assert pad_ok, "pad nibble of an odd-length tensor is not zero"
+    return CodeReport(n, int(near.sum()), int(diff.sum()), pad_ok)
+
+
+def _check_nonfinite(got: np.ndarray, ref: np.ndarray, mask: np.ndarray, what: str):
+    if not mask.any():
+        return
+    g, r = got[mask], ref[mask]
+    assert (np.isnan(g) == np.isnan(r)).all(), f"{what}: NaN pattern differs on non-finite inputs"
+    fin = ~np.isnan(r)
+    assert (g[fin] == r[fin]).all(), f"{what}: infinities differ on non-finite inputs"
+
+
+def check_values(got_storage: np.ndarray, ref: np.ndarray, dtype: int, what: str,
+                 finite_in: np.ndarray | None = None, skip: np.ndarray | None = None) -> float:
+    """Compare an output tensor (storage form) with the oracle's doubles.
+
+    `what` is "y" or "dx" and selects the tolerance.  `finite_in` marks elements
+    whose inputs were finite (others only need the same kind of result); `skip`
+    marks elements excluded altogether.  Returns the worst error in units of
+    the tolerance.
+    """
+    got = wl.storage_to_f64(got_storage, dtype)
+    n = ref.shape[0]
+    assert got.shape == (n,)
+    ok_in = np.ones(n, bool) if finite_in is None else finite_in.copy()
+    if skip is not None:
+        _check_nonfinite(got, ref, ~ok_in & ~skip, what)
+        ok_in &= ~skip
+    else:
+        _check_nonfinite(got, ref, ~ok_in, what)
+    # dx = dy * D with D up to 1.10 may exceed the largest storage value: there the
+    # correctly rounded result is an infinity of the same sign (or the largest finite).
+    top = 3.4028234663852886e38 if dtype == wl.F32 else 3.3895313892515355e38
+    over = np.abs(ref) > top
+    with np.errstate(invalid="ignore"):
+        err = np.abs(got - ref)
+    if over.any():
+        assert (np.sign(got[over]) == np.sign(ref[over])).all() and (np.abs(got[over]) >= top).all()
+        err[over] = 0.0
+    if dtype == wl.F32:
+        rel = 1e-6 if what == "y" else 1e-5
+        tol = rel * np.maximum(np.abs(ref), FLT_MIN)
+    else:
+        tol = (1.0 if what == "y" else 2.0) * bf16_ulp(ref)
+    with np.errstate(invalid="ignore"):
+        ratio = np.where(ok_in, err / tol, 0.0)
+    worst = float(np.nanmax(ratio)) if n else 0.0
+    assert not np.isnan(ratio[ok_in]).any(), f"{what}: NaN produced from finite input"
+    if worst > 1.0:
+        i = int(np.nanargmax(ratio))
+        raise AssertionError(
+            f"{what}: element {i} gpu={got[i]!r} oracle={ref[i]!r} err={err[i]:.3e} tol={tol[i]:.3e} "
+            f"({worst:.2f}x the tolerance; {(ratio > 1).sum()} elements out)")
+    return worst

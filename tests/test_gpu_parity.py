@@ -1,0 +1,202 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle on identical seeded inputs -- element by element at sizes that span
+several tiles and ragged tails, exhaustively over the bf16 domain, on special
+values, on unaligned and in-place buffers, and at every workload's full size."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_08154_amd import s2a
+from paper_2503_08154_amd import workloads as wl
+
+import gpu_util as gu
+import parity
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [wl.F32, wl.BF16]
+# lane-vector = 16 B (4 fp32 / 8 bf16); block strip = 256 lanes x 4 vectors
+SIZES = [0, 1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 255, 256, 257, 1023,
+         4095, 4096, 4097, 8191, 8192, 8193, 8192 * 3 + 5, 65536 + 1, 3 * 8192 * 4 + 8191, 302592]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _init():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    s2a.qtable_init(16)
+
+
+def _fwd_bwd_check(x, dy, dtype, report=None, **kw):
+    n = x.shape[0]
+    y_ref, code_ref, packed_ref, near = oracle.fwd(x, dtype, band=parity.BAND)
+    y, packed = gu.run_fwd(x, dtype, **kw)
+    finite = np.isfinite(wl.storage_to_f64(x, dtype))
+    rep = parity.check_codes(packed, code_ref, near, n)
+    wy = parity.check_values(y, y_ref, dtype, "y", finite_in=finite)
+    # backward in isolation: the oracle's codes in, every element checked
+    dx_ref = oracle.bwd(dy, dtype, packed_ref)
+    dx = gu.run_bwd(dy, packed_ref, dtype, **kw)
+    fin_dy = np.isfinite(wl.storage_to_f64(dy, dtype))
+    wdx = parity.check_values(dx, dx_ref, dtype, "dx", finite_in=fin_dy)
+    # backward on the GPU's own codes: elements whose code legitimately differs are skipped
+    if rep.differing:
+        dx2 = gu.run_bwd(dy, packed, dtype, **kw)
+        differs = parity.unpack(packed, n) != code_ref
+        parity.check_values(dx2, dx_ref, dtype, "dx", finite_in=fin_dy, skip=differs)
+    if report is not None:
+        report.append((n, rep.flagged, rep.differing, wy, wdx))
+    return rep, wy, wdx
+
+
+def test_table_through_the_kernel():
+    """dy = 1 and codes 0..15 recover the derivative table exactly (fp32)."""
+    _, deriv, _ = oracle.table()
+    packed = np.array([0x10, 0x32, 0x54, 0x76, 0x98, 0xBA, 0xDC, 0xFE], np.uint8)
+    dx = gu.run_bwd(np.ones(16, np.float32), packed, wl.F32)
+    np.testing.assert_array_equal(dx, deriv.astype(np.float32))
+    xhat = oracle.table()[0].astype(np.float32)
+    y, codes = gu.run_fwd(xhat, wl.F32)
+    np.testing.assert_array_equal(codes, packed)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("n", SIZES)
+def test_sizes(dtype, n):
+    x = wl.draw_x(n, "student_t", 2.0, dtype, seed=1000 + n)
+    dy = wl.draw_dy(n, 1.0, dtype, seed=2000 + n)
+    _fwd_bwd_check(x, dy, dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("n", [1, 9, 33, 4097, 8192 * 2 + 3, 100001])
+@pytest.mark.parametrize("off", [(1, 0), (0, 1), (1, 1), (3, 3)])
+def test_unaligned_pointers(dtype, n, off):
+    x = wl.draw_x(n, "normal", 1.5, dtype, seed=31 + n)
+    dy = wl.draw_dy(n, 1e-2, dtype, seed=32 + n)
+    _fwd_bwd_check(x, dy, dtype, offset_elems=off[0], code_offset=off[1])
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("n", [17, 8192 * 5 + 1, 302592])
+@pytest.mark.parametrize("off", [0, 1])
+def test_in_place(dtype, n, off):
+    x = wl.draw_x(n, "normal_outliers", 1.5, dtype, seed=41 + n)
+    dy = wl.draw_dy(n, 1e-2, dtype, seed=42 + n)
+    _fwd_bwd_check(x, dy, dtype, inplace=True, offset_elems=off)
+
+
+def test_exhaustive_bf16_domain():
+    """All 65,536 bf16 bit patterns as x (NaNs and infinities included), and as dy
+    against every code."""
+    bits = np.arange(65536, dtype=np.uint16)
+    y_ref, code_ref, packed_ref, near = oracle.fwd(bits, wl.BF16, band=parity.BAND)
+    y, packed = gu.run_fwd(bits, wl.BF16)
+    finite = np.isfinite(wl.bf16_bits_to_f32(bits))
+    rep = parity.check_codes(packed, code_ref, near, 65536)
+    parity.check_values(y, y_ref, wl.BF16, "y", finite_in=finite)
+    print(f"\n[exhaustive bf16] {rep}")
+    # non-finite x: NaN -> code 0, +inf -> 15, -inf -> 0 (checked above through the oracle's codes)
+    assert parity.unpack(packed, 65536)[0x7FC0] == 0 and parity.unpack(packed, 65536)[0x7F80] == 15
+    for shift in range(16):
+        codes = ((np.arange(65536) + shift) % 16).astype(np.uint8)
+        pk = (codes[0::2] | (codes[1::2] << 4)).astype(np.uint8)
+        dx_ref = oracle.bwd(bits, wl.BF16, pk)
+        dx = gu.run_bwd(bits, pk, wl.BF16)
+        parity.check_values(dx, dx_ref, wl.BF16, "dx", finite_in=finite)
+
+
+def test_fp32_special_values():
+    _, _, bounds = oracle.table()
+    b32 = bounds.astype(np.float32)
+    near_bounds = np.concatenate([np.nextafter(b32, np.float32(-9), dtype=np.float32),
+                                  b32, np.nextafter(b32, np.float32(9), dtype=np.float32),
+                                  b32 + np.float32(3e-6), b32 - np.float32(3e-6)])
+    tiny = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-38, -1e-38, 1.17549435e-38, -1.17549435e-38,
+                     1e-30, -1e-30, 1e-10, -1e-10, 2.0 ** -24, -2.0 ** -24, 2.0 ** -60, -2.0 ** -60], np.float32)
+    huge = np.array([3.4028235e38, -3.4028235e38, 1e30, -1e30, 129.0, -129.0, 128.0, -128.0, 127.99, -127.99,
+                     np.inf, -np.inf, np.nan], np.float32)
+    # the range where y leaves the normal fp32 numbers and then underflows
+    under = -np.linspace(20.0, 70.0, 5001).astype(np.float32)
+    grid = np.linspace(-30.0, 30.0, 60001).astype(np.float32)
+    levels = np.array([-2.0, 2.0, np.nextafter(np.float32(2), np.float32(3)), np.nextafter(np.float32(-2), np.float32(-3)),
+                       -1.0, 1.0, 0.5, -0.5], np.float32)
+    x = np.concatenate([near_bounds, tiny, huge, under, grid, levels]).astype(np.float32)
+    dy = wl.draw_dy(x.shape[0], 1.0, wl.F32, seed=5)
+    dy[:8] = np.array([0.0, -0.0, 1e-45, 3.4028235e38, -3.4028235e38, np.inf, -np.inf, np.nan], np.float32)
+    rep, wy, wdx = _fwd_bwd_check(x, dy, wl.F32)
+    print(f"\n[fp32 special] {rep} worst y {wy:.3f} worst dx {wdx:.3f} (fractions of the tolerance)")
+    # expected by construction: the 15 decision points and their fp32 neighbours are in the band
+    assert rep.flagged >= 45
+
+
+def test_fp32_dense_sweep_accuracy():
+    """2^22 fp32 values log-spaced in magnitude over both signs: y within 1e-6 relative."""
+    m = 1 << 21
+    mag = np.exp2(np.linspace(-30.0, 7.0, m)).astype(np.float32)
+    x = np.concatenate([mag, -mag])
+    dy = wl.draw_dy(x.shape[0], 1e-2, wl.F32, seed=6)
+    rep, wy, wdx = _fwd_bwd_check(x, dy, wl.F32)
+    print(f"\n[fp32 sweep] {rep} worst y {wy:.3f} worst dx {wdx:.3f} (fractions of the tolerance)")
+
+
+def test_side_stream():
+    s = torch.cuda.Stream()
+    n = 8192 * 7 + 13
+    x = wl.draw_x(n, "normal", 1.0, wl.BF16, seed=77)
+    dy = wl.draw_dy(n, 1e-2, wl.BF16, seed=78)
+    _fwd_bwd_check(x, dy, wl.BF16, stream=s)
+
+
+def test_outputs_are_fully_overwritten():
+    """Stale 0xFF bytes in y / codes / dx never survive, including the pad nibble."""
+    for dtype in DTYPES:
+        for n in (1, 7, 8193, 40001):
+            x = wl.draw_x(n, "normal", 1.0, dtype, seed=n)
+            es = gu.esize(dtype)
+            bx = gu.Buf(n * es).upload(x)
+            by = gu.Buf(n * es, fill=0xFF)
+            bc = gu.Buf((n + 1) // 2, fill=0xFF)
+            s2a.act_fwd(bx.ptr, by.ptr, bc.ptr, n, dtype, torch.cuda.current_stream().cuda_stream)
+            y_ref, code_ref, packed_ref, near = oracle.fwd(x, dtype, band=parity.BAND)
+            parity.check_codes(bc.download(np.uint8), code_ref, near, n)
+            parity.check_values(by.download(gu.storage_np(dtype)), y_ref, dtype, "y")
+
+
+WORKLOAD_CASES = [("tiny", 0, 0), ("vit_b16", 0, 0), ("vit_b16", 11, 0), ("vit_l16", 0, 0), ("vit_l16", 23, 0),
+                  ("swin_b", 0, 0), ("swin_b", 0, 1), ("swin_b", 0, 2), ("swin_b", 0, 3),
+                  ("vit_g14", 0, 0), ("vit_g14_f32", 0, 0)]
+
+
+@pytest.mark.parametrize("name,layer,stage", WORKLOAD_CASES)
+def test_workload_full_size(name, layer, stage):
+    """Every configuration at its full size, in the launch configuration the benchmark
+    times (256-byte aligned buffers, the caller's stream), every element checked."""
+    w = wl.WORKLOADS[name]
+    x, dy = wl.layer_inputs(w, layer, stage)
+    n = x.shape[0]
+    es = gu.esize(w.dtype)
+    st = torch.cuda.current_stream().cuda_stream
+    tx = torch.from_numpy(x.view(np.uint8)).cuda()
+    ty = torch.empty_like(tx)
+    tc = torch.empty((n + 1) // 2, dtype=torch.uint8, device="cuda")
+    s2a.act_fwd(tx.data_ptr(), ty.data_ptr(), tc.data_ptr(), n, w.dtype, st)
+    torch.cuda.synchronize()
+    y = ty.cpu().numpy().view(gu.storage_np(w.dtype))
+    packed = tc.cpu().numpy()
+    del ty
+    y_ref, code_ref, packed_ref, near = oracle.fwd(x, w.dtype, band=parity.BAND)
+    rep = parity.check_codes(packed, code_ref, near, n)
+    wy = parity.check_values(y, y_ref, w.dtype, "y")
+    del y, y_ref
+    tdy = torch.from_numpy(dy.view(np.uint8)).cuda()
+    tdx = torch.empty_like(tdy)
+    s2a.act_bwd(tdy.data_ptr(), tc.data_ptr(), tdx.data_ptr(), n, w.dtype, st)
+    torch.cuda.synchronize()
+    dx = tdx.cpu().numpy().view(gu.storage_np(w.dtype))
+    dx_ref = oracle.bwd(dy, w.dtype, packed_ref)
+    differs = parity.unpack(packed, n) != code_ref
+    wdx = parity.check_values(dx, dx_ref, w.dtype, "dx", skip=differs if rep.differing else None)
+    print(f"\n[{name} layer {layer} stage {stage}] n={n} {rep} worst y {wy:.3f} worst dx {wdx:.3f} "
+          f"(fractions of the tolerance)")
+    assert es * n == x.nbytes
