@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the 4-bit GELU activation path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole hot path over one batch of synthetic
+activations: the forward kernel over every layer (launch) of the workload,
+then the backward kernel over the same layers in reverse, all enqueued on one
+stream with no host synchronisation in between.  Every layer has its own
+x / y / codes / dy / dx buffers, so each launch streams cold HBM (the working
+set is several GB, far beyond the 256 MB on-die cache).  Inputs are resident
+in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is algorithmic bytes moved per second, fwd+bwd:
+(2*e + 0.5) bytes per element and direction, e = element size.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2503_08154_amd import s2a  # noqa: E402
+from paper_2503_08154_amd import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
+
+# HBM bytes per launch seen by the memory-side counters (rocprofv3 --pmc FETCH_SIZE
+# and WRITE_SIZE, each scaled by what the same counter reads for a plain copy of
+# known size).  Measured offline; the summaries are under profiles/.  None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def esize(dtype: int) -> int:
+    return 4 if dtype == wl.F32 else 2
+
+
+def bytes_per_direction(n: int, dtype: int) -> float:
+    return (2 * esize(dtype) + 0.5) * n
+
+
+class Layer:
+    """Device buffers of one launch (torch is used only to own memory)."""
+
+    def __init__(self, torch, x: np.ndarray, dy: np.ndarray, dtype: int):
+        self.n = int(x.shape[0])
+        self.dtype = dtype
+        self.x = torch.from_numpy(x.view(np.uint8)).cuda()
+        self.dy = torch.from_numpy(dy.view(np.uint8)).cuda()
+        self.y = torch.empty_like(self.x)
+        self.dx = torch.empty_like(self.dy)
+        self.codes = torch.empty((self.n + 1) // 2, dtype=torch.uint8, device="cuda")
+        self.p = tuple(t.data_ptr() for t in (self.x, self.y, self.codes, self.dy, self.dx))
+
+
+def build_layers(torch, w: wl.Workload, distinct_seeds: bool):
+    """One Layer per (layer, stage) of the workload, in forward order."""
+    jobs = [(l, s) for l in range(w.layers) for s in range(len(w.shapes))]
+    if distinct_seeds:
+        with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as ex:
+            host = list(ex.map(lambda j: wl.layer_inputs(w, j[0], j[1]), jobs))
+    else:  # timing does not depend on the values: draw each stage once, reuse per layer
+        per_stage = [wl.layer_inputs(w, 0, s) for s in range(len(w.shapes))]
+        host = [per_stage[s] for (_, s) in jobs]
+    return [Layer(torch, x, dy, w.dtype) for (x, dy) in host]
+
+
+def run_step(layers, stream: int, ev=None):
+    """fwd over all layers, then bwd in reverse; optional (e0, e1, e2) events around the phases."""
+    if ev:
+        ev[0].record()
+    for L in layers:
+        s2a.act_fwd(L.p[0], L.p[1], L.p[2], L.n, L.dtype, stream)
+    if ev:
+        ev[1].record()
+    for L in reversed(layers):
+        s2a.act_bwd(L.p[3], L.p[2], L.p[4], L.n, L.dtype, stream)
+    if ev:
+        ev[2].record()
+
+
+def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds: bool):
+    layers = build_layers(torch, w, distinct_seeds)
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(warmup):
+        run_step(layers, stream)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        run_step(layers, stream, events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in events)
+    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in events)
+    launches = steps * len(layers)
+    n_total = sum(L.n for L in layers)
+    bytes_dir = sum(bytes_per_direction(L.n, L.dtype) for L in layers)
+    res = {
+        "ms_per_step": wall * 1e3 / steps,
+        "elements_per_step": n_total,
+        "bytes_per_step": 2 * bytes_dir,
+        "launches_per_phase": len(layers),
+        "fwd_us_per_launch": fwd_ms * 1e3 / launches,
+        "bwd_us_per_launch": bwd_ms * 1e3 / launches,
+        "fwd_gbs": bytes_dir * steps / (fwd_ms * 1e-3) / 1e9,
+        "bwd_gbs": bytes_dir * steps / (bwd_ms * 1e-3) / 1e9,
+        "bytes_per_launch": bytes_dir / len(layers),
+    }
+    del layers
+    torch.cuda.empty_cache()
+    return res
+
+
+def roofline_of(res, w: wl.Workload):
+    """Roofline entry of the slower of the two kernels."""
+    which = "fwd" if res["fwd_us_per_launch"] >= res["bwd_us_per_launch"] else "bwd"
+    achieved = res[f"{which}_gbs"]
+    dt = "bf16" if w.dtype == wl.BF16 else "f32"
+    return {
+        "kernel": f"s2a::{which}_kernel<{dt}>",
+        "bound": "hbm",
+        "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC.get((w.name, which)),
+        "us_per_launch": round(res[f"{which}_us_per_launch"], 2),
+        "algorithmic_bytes_per_launch": res["bytes_per_launch"],
+        "other_kernel": {
+            "kernel": f"s2a::{'bwd' if which == 'fwd' else 'fwd'}_kernel<{dt}>",
+            "achieved": round(res["bwd_gbs" if which == "fwd" else "fwd_gbs"], 1),
+            "frac": round(res["bwd_gbs" if which == "fwd" else "fwd_gbs"] / HBM_PEAK_GBS, 4),
+            "us_per_launch": round(res["bwd_us_per_launch" if which == "fwd" else "fwd_us_per_launch"], 2),
+            "traffic": MEASURED_TRAFFIC.get((w.name, "bwd" if which == "fwd" else "fwd")),
+        },
+    }
+
+
+def cpu_baseline(w: wl.Workload, target_cpu_seconds: float = 12.0):
+    """The CPU oracle, as it stands, over one layer of the workload, chunked over the host cores."""
+    import oracle  # test infrastructure; used here only as the reported CPU baseline
+
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    cores = max(1, min(avail, int(os.environ.get("OMP_NUM_THREADS", "16")), 16))
+    x, dy = wl.layer_inputs(w, 0, 0)
+    n = x.shape[0]
+    edges = [(n * i // cores) & ~1 for i in range(cores)] + [n]  # even starts: no shared code byte
+    oracle.table()  # load the library outside the timed region
+
+    def work(i):
+        a, b = edges[i], edges[i + 1]
+        _, _, packed, _ = oracle.fwd(x[a:b], w.dtype, want_near=False)
+        oracle.bwd(dy[a:b], w.dtype, packed)
+
+    reps, cpu_seconds, wall = 0, 0.0, 0.0
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        while cpu_seconds < target_cpu_seconds and reps < 8:
+            t0 = time.perf_counter()
+            list(ex.map(work, range(cores)))
+            dt = time.perf_counter() - t0
+            wall += dt
+            cpu_seconds += dt * cores
+            reps += 1
+    moved = 2 * bytes_per_direction(n, w.dtype) * reps
+    return {
+        "value": round(moved / wall / 1e9, 3),
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"one {w.name} layer ({n} elements) fwd+bwd, {reps} repetitions, "
+                  f"split into {cores} contiguous chunks, one thread each",
+        "elements_per_s": round(n * reps / wall, 1),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vit_b16", choices=sorted(wl.WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-targets", action="store_true",
+                    help="skip the extra per-kernel roofline entries at the ViT-L / ViT-G shapes")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this path is built and measured on ONE GPU; run with --gpus 1 "
+                 "(the kernels are element-wise: more GPUs would each run the same launch on a shard)")
+
+    import torch
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the activation path has no CPU fallback")
+    torch.cuda.set_device(0)
+    s2a.qtable_init(16)
+
+    w = wl.WORKLOADS[args.workload]
+    res = time_workload(torch, w, args.steps, args.warmup, distinct_seeds=True)
+    value = res["bytes_per_step"] / (res["ms_per_step"] * 1e-3) / 1e9
+    dt = "bf16" if w.dtype == wl.BF16 else "f32"
+    out = {
+        "metric": "GB/s and % of HBM peak for 4-bit GELU fwd+bwd (elements/s), 1xMI355X",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(res["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",  # arithmetic type of the path; storage is in config
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: {dt} " + " + ".join("x".join(map(str, s)) for s in w.shapes)
+                        + f", {w.layers} layer(s) back to back, fwd then bwd",
+            "storage_dtype": dt,
+            "elements_per_step": res["elements_per_step"],
+            "launches_per_step": 2 * res["launches_per_phase"],
+        },
+        "elements_per_s": round(res["elements_per_step"] / (res["ms_per_step"] * 1e-3), 1),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "roofline": roofline_of(res, w),
+    }
+    if not args.no_targets:
+        targets = {}
+        for name in ("vit_l16", "vit_g14", "vit_g14_f32"):
+            if name == w.name:
+                continue
+            tw = wl.WORKLOADS[name]
+            # single-launch workloads get 8 buffer sets so that every launch reads cold HBM
+            if tw.layers == 1:
+                tw = wl.Workload(tw.name, tw.index, tw.dtype, tw.shapes, 8, tw.dist, tw.scale, tw.dy_scale)
+            r = time_workload(torch, tw, max(5, args.steps // 2), 2, distinct_seeds=False)
+            rf = roofline_of(r, tw)
+            targets[name] = {
+                "fwd_gbs": round(r["fwd_gbs"], 1), "bwd_gbs": round(r["bwd_gbs"], 1),
+                "fwd_frac": round(r["fwd_gbs"] / HBM_PEAK_GBS, 4), "bwd_frac": round(r["bwd_gbs"] / HBM_PEAK_GBS, 4),
+                "fwd_us": round(r["fwd_us_per_launch"], 2), "bwd_us": round(r["bwd_us_per_launch"], 2),
+                "buffer_sets": tw.layers, "slower": rf["kernel"],
+            }
+        out["target_shapes"] = targets
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -103,16 +103,21 @@ def _storage(a: np.ndarray, dtype: int) -> np.ndarray:
     return a
 
 
-def fwd(x: np.ndarray, dtype: int, band: float = 1e-6):
-    """Forward pass.  Returns (y float64[n], code uint8[n], packed uint8[(n+1)//2], near uint8[n])."""
+def fwd(x: np.ndarray, dtype: int, band: float = 1e-6, want_near: bool = True):
+    """Forward pass.  Returns (y float64[n], code uint8[n], packed uint8[(n+1)//2], near uint8[n]).
+
+    `near` flags inputs within `band` of a decision point (test bookkeeping, not part
+    of the method); with want_near=False it is skipped and returned as None.
+    """
     x = _storage(x, dtype)
     n = x.shape[0]
     y = np.empty(n, np.float64)
     code = np.empty(n, np.uint8)
     packed = np.empty((n + 1) // 2, np.uint8)
-    near = np.empty(n, np.uint8)
+    near = np.empty(n, np.uint8) if want_near else None
     rc = _load().s2a_oracle_fwd(x.ctypes.data, dtype, n, y.ctypes.data, code.ctypes.data,
-                                packed.ctypes.data, near.ctypes.data, float(band))
+                                packed.ctypes.data, near.ctypes.data if want_near else None,
+                                float(band))
     if rc != 0:
         raise ValueError("s2a_oracle_fwd rejected its arguments")
     return y, code, packed, near

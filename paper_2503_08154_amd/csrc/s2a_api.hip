@@ -62,6 +62,7 @@ template <bool BF16, int UNROLL>
 int launch_fwd(const void* x, void* y, uint8_t* codes, int64_t n, hipStream_t st)
 {
     constexpr int EPV = BF16 ? 8 : 4;
+    (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
     if (aligned(x, 16) && aligned(y, 16) && aligned(codes, 4)) {
         int64_t nvec = n / EPV;
         int64_t slots = nvec + (n % EPV != 0);
@@ -80,6 +81,7 @@ template <bool BF16, int UNROLL>
 int launch_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, hipStream_t st)
 {
     constexpr int EPV = BF16 ? 8 : 4;
+    (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
     if (aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 4)) {
         int64_t nvec = n / EPV;
         int64_t slots = nvec + (n % EPV != 0);
