@@ -9,10 +9,6 @@
 
 namespace {
 
-// Launch shape of the vector kernels: vectors (16 B of x) per lane.
-constexpr int kUnrollBf16 = 4;
-constexpr int kUnrollF32 = 4;
-constexpr bool kNonTemporal = true;
 
 struct TableState {
     bool ready = false;
@@ -58,7 +54,7 @@ unsigned pair_grid(int64_t n)
     return (unsigned)(blocks < cap ? blocks : cap);
 }
 
-template <bool BF16, int UNROLL>
+template <bool BF16>
 int launch_fwd(const void* x, void* y, uint8_t* codes, int64_t n, hipStream_t st)
 {
     constexpr int EPV = BF16 ? 8 : 4;
@@ -66,10 +62,9 @@ int launch_fwd(const void* x, void* y, uint8_t* codes, int64_t n, hipStream_t st
     if (aligned(x, 16) && aligned(y, 16) && aligned(codes, 4)) {
         int64_t nvec = n / EPV;
         int64_t slots = nvec + (n % EPV != 0);
-        int64_t per_block = (int64_t)s2a::kBlock * UNROLL;
-        int64_t blocks = (slots + per_block - 1) / per_block;
+        int64_t blocks = (slots + s2a::kWave - 1) / s2a::kWave;
         if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
-        s2a::fwd_kernel<BF16, UNROLL, kNonTemporal><<<dim3((unsigned)blocks), dim3(s2a::kBlock), 0, st>>>(
+        s2a::fwd_kernel<BF16><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(
             (const s2a::u32x4*)x, (s2a::u32x4*)y, codes, n, nvec);
     } else {
         s2a::fwd_kernel_unaligned<BF16><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(x, y, codes, n);
@@ -77,7 +72,7 @@ int launch_fwd(const void* x, void* y, uint8_t* codes, int64_t n, hipStream_t st
     return hipGetLastError() == hipSuccess ? S2A_OK : S2A_ERR_LAUNCH;
 }
 
-template <bool BF16, int UNROLL>
+template <bool BF16>
 int launch_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, hipStream_t st)
 {
     constexpr int EPV = BF16 ? 8 : 4;
@@ -85,10 +80,9 @@ int launch_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, hipStr
     if (aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 4)) {
         int64_t nvec = n / EPV;
         int64_t slots = nvec + (n % EPV != 0);
-        int64_t per_block = (int64_t)s2a::kBlock * UNROLL;
-        int64_t blocks = (slots + per_block - 1) / per_block;
+        int64_t blocks = (slots + s2a::kWave - 1) / s2a::kWave;
         if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
-        s2a::bwd_kernel<BF16, UNROLL, kNonTemporal><<<dim3((unsigned)blocks), dim3(s2a::kBlock), 0, st>>>(
+        s2a::bwd_kernel<BF16><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(
             (const s2a::u32x4*)dy, codes, (s2a::u32x4*)dx, g_table.dev, n, nvec);
     } else {
         s2a::bwd_kernel_unaligned<BF16><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(
@@ -125,8 +119,8 @@ int s2a_act_fwd(const void* x, void* y, uint8_t* codes, int64_t n, int dtype, vo
     int rc = check_common(x, y, codes, n, dtype);
     if (rc != S2A_OK || n == 0) return rc;
     hipStream_t st = (hipStream_t)stream;
-    return dtype == S2A_BF16 ? launch_fwd<true, kUnrollBf16>(x, y, codes, n, st)
-                             : launch_fwd<false, kUnrollF32>(x, y, codes, n, st);
+    return dtype == S2A_BF16 ? launch_fwd<true>(x, y, codes, n, st)
+                             : launch_fwd<false>(x, y, codes, n, st);
 }
 
 int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int dtype, void* stream)
@@ -134,8 +128,8 @@ int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int d
     int rc = check_common(dy, codes, dx, n, dtype);
     if (rc != S2A_OK || n == 0) return rc;
     hipStream_t st = (hipStream_t)stream;
-    return dtype == S2A_BF16 ? launch_bwd<true, kUnrollBf16>(dy, codes, dx, n, st)
-                             : launch_bwd<false, kUnrollF32>(dy, codes, dx, n, st);
+    return dtype == S2A_BF16 ? launch_bwd<true>(dy, codes, dx, n, st)
+                             : launch_bwd<false>(dy, codes, dx, n, st);
 }
 
 const char* s2a_strerror(int code)

@@ -16,9 +16,9 @@ import parity
 pytestmark = pytest.mark.gpu
 
 DTYPES = [wl.F32, wl.BF16]
-# lane-vector = 16 B (4 fp32 / 8 bf16); block strip = 256 lanes x 4 vectors
-SIZES = [0, 1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 255, 256, 257, 1023,
-         4095, 4096, 4097, 8191, 8192, 8193, 8192 * 3 + 5, 65536 + 1, 3 * 8192 * 4 + 8191, 302592]
+# lane-vector = 16 B (4 fp32 / 8 bf16); one block = one wave of 64 vectors (256 fp32 / 512 bf16 elements)
+SIZES = [0, 1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 255, 256, 257, 259, 511, 512, 513, 519,
+         767, 1023, 1535, 4095, 4096, 4097, 8191, 8192, 8193, 8192 * 3 + 5, 65536 + 1, 3 * 8192 * 4 + 8191, 302592]
 
 
 @pytest.fixture(scope="module", autouse=True)
