@@ -37,7 +37,13 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 # HBM bytes per launch seen by the memory-side counters (rocprofv3 --pmc FETCH_SIZE
 # and WRITE_SIZE, each scaled by what the same counter reads for a plain copy of
 # known size).  Measured offline; the summaries are under profiles/.  None = not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # (workload, kernel): bytes per launch -- profiles/fwd_bwd_kernels_hbm_traffic_pmc.txt
+    ("vit_b16", "fwd"): 174292256, ("vit_b16", "bwd"): 174287059,
+    ("vit_l16", "fwd"): 232384067, ("vit_l16", "bwd"): 232382979,
+    ("vit_g14", "fwd"): 303167841, ("vit_g14", "bwd"): 303163114,
+    ("vit_g14_f32", "fwd"): 572655648, ("vit_g14_f32", "bwd"): 572650524,
+}
 
 
 def esize(dtype: int) -> int:
@@ -244,7 +250,7 @@ def main():
             # single-launch workloads get 8 buffer sets so that every launch reads cold HBM
             if tw.layers == 1:
                 tw = wl.Workload(tw.name, tw.index, tw.dtype, tw.shapes, 8, tw.dist, tw.scale, tw.dy_scale)
-            r = time_workload(torch, tw, max(5, args.steps // 2), 2, distinct_seeds=False)
+            r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False)
             rf = roofline_of(r, tw)
             targets[name] = {
                 "fwd_gbs": round(r["fwd_gbs"], 1), "bwd_gbs": round(r["bwd_gbs"], 1),
