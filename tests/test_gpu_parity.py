@@ -200,3 +200,56 @@ def test_workload_full_size(name, layer, stage):
     print(f"\n[{name} layer {layer} stage {stage}] n={n} {rep} worst y {wy:.3f} worst dx {wdx:.3f} "
           f"(fractions of the tolerance)")
     assert es * n == x.nbytes
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_more_than_2_31_elements(dtype):
+    """n just above 2^31 (64-bit indexing everywhere, ragged tail): a seeded tile is
+    repeated on the device, and 256 sampled spans of ~4096 outputs (both ends and the
+    2^31 crossing included) are checked one by one against the oracle."""
+    tile_n = (1 << 22) + 3                      # odd: every repetition has a different alignment
+    n = (1 << 31) + 8 * 64 * 3 + 5              # odd: pad nibble, leftover elements
+    tile_x = wl.draw_x(tile_n, "student_t", 2.0, dtype, seed=4242)
+    tile_dy = wl.draw_dy(tile_n, 1e-2, dtype, seed=4243)
+    reps = -(-n // tile_n)
+
+    def tiled(tile):
+        t = torch.from_numpy(tile.view(np.int16) if dtype == wl.BF16 else tile).cuda()
+        return t.repeat(reps)[:n]
+
+    tx = tiled(tile_x)
+    ty = torch.empty_like(tx)
+    tc = torch.empty((n + 1) // 2, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    s2a.act_fwd(tx.data_ptr(), ty.data_ptr(), tc.data_ptr(), n, dtype, st)
+    torch.cuda.synchronize()
+
+    # Spans are copied back slice by slice (plain device-to-host copies): advanced
+    # indexing of a tensor this large faults inside torch's own index kernel here.
+    g = np.random.default_rng(99)
+    spans = [(0, 4096), (n - 5001, 5001), ((1 << 31) - 2048, 3072)]   # the tensor ends 1541 past 2^31
+    spans += [(int(a) & ~1, 4096) for a in g.integers(0, n - 4096, 253)]   # even starts own whole code bytes
+
+    def fetch(t):
+        return np.concatenate([t[a:a + m].cpu().numpy() for a, m in spans]).view(gu.storage_np(dtype))
+
+    pos = np.concatenate([np.arange(a, a + m, dtype=np.int64) for a, m in spans])
+    x_s = tile_x[pos % tile_n].copy()
+    dy_s = tile_dy[pos % tile_n].copy()
+    y_ref, code_ref, _, near = oracle.fwd(x_s, dtype, band=parity.BAND)
+    parity.check_values(fetch(ty), y_ref, dtype, "y")
+    code_s = np.concatenate([parity.unpack(tc[a // 2:(a + m + 1) // 2].cpu().numpy(), m) for a, m in spans])
+    diff = code_s != code_ref
+    assert not (diff & (near == 0)).any()
+    assert (tc[-1:].cpu().numpy()[0] >> 4) == 0  # pad nibble of the odd-length tensor
+    del ty
+    tdy = tiled(tile_dy)
+    tdx = torch.empty_like(tdy)
+    s2a.act_bwd(tdy.data_ptr(), tc.data_ptr(), tdx.data_ptr(), n, dtype, st)
+    torch.cuda.synchronize()
+    # the oracle's backward reads packed codes: pack each span's oracle codes with the oracle itself
+    dx_ref = np.concatenate([oracle.bwd(dy_s[o:o + m].copy(), dtype, oracle.fwd(x_s[o:o + m].copy(), dtype)[2])
+                             for o, m in zip(np.cumsum([0] + [m for _, m in spans[:-1]]), [m for _, m in spans])])
+    parity.check_values(fetch(tdx), dx_ref, dtype, "dx", skip=diff)
+    print(f"\n[n={n} dtype={dtype}] checked {pos.shape[0]} sampled elements, in-band {int(near.sum())}, "
+          f"differing {int(diff.sum())}")
