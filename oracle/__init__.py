@@ -57,6 +57,16 @@ def _load():
         lib.s2a_oracle_fwd.argtypes = [vp, i, i64, vp, vp, vp, vp, d]
         lib.s2a_oracle_bwd.restype = i
         lib.s2a_oracle_bwd.argtypes = [vp, i, vp, i64, vp]
+        lib.s2a_oracle_range.restype = i
+        lib.s2a_oracle_range.argtypes = [vp, i, i64, vp, vp]
+        lib.s2a_oracle_quantize_dyn.restype = i
+        lib.s2a_oracle_quantize_dyn.argtypes = [d, d, d]
+        lib.s2a_oracle_dequantize_dyn.restype = d
+        lib.s2a_oracle_dequantize_dyn.argtypes = [i, d, d]
+        lib.s2a_oracle_fwd_dyn.restype = i
+        lib.s2a_oracle_fwd_dyn.argtypes = [vp, i, i64, vp, vp, vp, vp, vp, vp, d]
+        lib.s2a_oracle_bwd_dyn.restype = i
+        lib.s2a_oracle_bwd_dyn.argtypes = [vp, i, vp, i64, d, d, vp]
         _lib = lib
     return _lib
 
@@ -133,4 +143,46 @@ def bwd(dy: np.ndarray, dtype: int, packed: np.ndarray) -> np.ndarray:
     rc = _load().s2a_oracle_bwd(dy.ctypes.data, dtype, packed.ctypes.data, n, dx.ctypes.data)
     if rc != 0:
         raise ValueError("s2a_oracle_bwd rejected its arguments")
+    return dx
+
+
+# ---- measured-range variant (Eq. 8 with the tensor's own min and max) ----
+
+def quantize_dyn(x: float, qmin: float, qscale: float) -> int:
+    return _load().s2a_oracle_quantize_dyn(float(x), float(qmin), float(qscale))
+
+
+def dequantize_dyn(q: int, qmin: float, qscale: float) -> float:
+    return _load().s2a_oracle_dequantize_dyn(int(q), float(qmin), float(qscale))
+
+
+def fwd_dyn(x: np.ndarray, dtype: int, band: float = 1e-6, want_near: bool = True):
+    """Forward pass with the measured range.
+    Returns (y, code, packed, near, qmin, qscale); qmin/qscale are Python floats."""
+    x = _storage(x, dtype)
+    n = x.shape[0]
+    y = np.empty(n, np.float64)
+    code = np.empty(n, np.uint8)
+    packed = np.empty((n + 1) // 2, np.uint8)
+    near = np.empty(n, np.uint8) if want_near else None
+    qmin = ctypes.c_double()
+    qscale = ctypes.c_double()
+    rc = _load().s2a_oracle_fwd_dyn(x.ctypes.data, dtype, n, y.ctypes.data, code.ctypes.data,
+                                    packed.ctypes.data, ctypes.addressof(qmin), ctypes.addressof(qscale),
+                                    near.ctypes.data if want_near else None, float(band))
+    if rc != 0:
+        raise ValueError("s2a_oracle_fwd_dyn rejected its arguments")
+    return y, code, packed, near, qmin.value, qscale.value
+
+
+def bwd_dyn(dy: np.ndarray, dtype: int, packed: np.ndarray, qmin: float, qscale: float) -> np.ndarray:
+    dy = _storage(dy, dtype)
+    n = dy.shape[0]
+    if packed.dtype != np.uint8 or packed.shape != ((n + 1) // 2,) or not packed.flags.c_contiguous:
+        raise TypeError("packed must be contiguous uint8 of length ceil(n/2)")
+    dx = np.empty(n, np.float64)
+    rc = _load().s2a_oracle_bwd_dyn(dy.ctypes.data, dtype, packed.ctypes.data, n, float(qmin),
+                                    float(qscale), dx.ctypes.data)
+    if rc != 0:
+        raise ValueError("s2a_oracle_bwd_dyn rejected its arguments")
     return dx

@@ -170,3 +170,93 @@ int s2a_oracle_bwd(const void *dy, int dtype, const uint8_t *packed, int64_t n, 
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Data-dependent range ("between the maximal and minimal value", GeLU
+ * paragraph read literally): Eq. 8's min and max are measured on the clipped
+ * tensor instead of being the clip limits.  One (min, scale) pair per tensor,
+ * stored beside the codes, as Eq. 9 needs both in the backward pass.
+ *
+ * Readings: the extremes are taken over the whole tensor (the paper names no
+ * granularity); NaN clips to -2 as above and therefore takes part in the
+ * minimum; a tensor whose clipped values are all equal has scale 0 and every
+ * code 0, so Eq. 9 returns that value exactly.
+ *
+ * Pins (tests/test_oracle_dyn_pins.py): equality with the fixed-range oracle
+ * whenever the tensor reaches both clip limits; exact rational arithmetic on
+ * small tensors; shift invariance of the codes; extremes map to codes 0 and
+ * 15; reconstruction within half a step; the degenerate tensor.
+ * ---------------------------------------------------------------------- */
+
+static double clip_x(double x) { return fmin(fmax(x, ORACLE_XMIN), ORACLE_XMAX); }
+
+/* min and scale of Eq. 8 for this tensor; returns 0, or -1 on bad arguments. */
+int s2a_oracle_range(const void *x, int dtype, int64_t n, double *qmin, double *qscale)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n < 0) return -1;
+    double lo = INFINITY, hi = -INFINITY;
+    for (int64_t i = 0; i < n; ++i) {
+        double xc = clip_x(load_elem(x, dtype, i));
+        if (xc < lo) lo = xc;
+        if (xc > hi) hi = xc;
+    }
+    if (n == 0) { lo = 0.0; hi = 0.0; }
+    *qmin = lo;
+    *qscale = (hi - lo) / (double)((1 << ORACLE_NBITS) - 1);
+    return 0;
+}
+
+/* Eq. 8 with a given (min, scale). */
+int s2a_oracle_quantize_dyn(double x, double qmin, double qscale)
+{
+    if (!(qscale > 0.0)) return 0;
+    double q = nearbyint((clip_x(x) - qmin) / qscale);
+    /* a value outside the range the scale was measured on still gets a valid code */
+    if (q < 0.0) q = 0.0;
+    if (q > 15.0) q = 15.0;
+    return (int)q;
+}
+
+/* Eq. 9 with a given (min, scale). */
+double s2a_oracle_dequantize_dyn(int q, double qmin, double qscale) { return (double)q * qscale + qmin; }
+
+/*
+ * Forward pass with the measured range.  Outputs as in s2a_oracle_fwd, plus
+ * the (min, scale) pair.  `near` flags inputs within `band` of a decision
+ * point qmin + (j + 1/2) * qscale.
+ */
+int s2a_oracle_fwd_dyn(const void *x, int dtype, int64_t n, double *y, uint8_t *code,
+                       uint8_t *packed, double *qmin, double *qscale, uint8_t *near, double band)
+{
+    if (s2a_oracle_range(x, dtype, n, qmin, qscale) != 0) return -1;
+    if (packed) memset(packed, 0, (size_t)((n + 1) / 2));
+    for (int64_t i = 0; i < n; ++i) {
+        double xi = load_elem(x, dtype, i);
+        int q = s2a_oracle_quantize_dyn(xi, *qmin, *qscale);
+        if (y) y[i] = s2a_oracle_gelu(xi);
+        if (code) code[i] = (uint8_t)q;
+        if (packed) packed[i / 2] |= (uint8_t)(q << (4 * (i & 1)));
+        if (near) {
+            double best = INFINITY;
+            for (int j = 0; j < 15; ++j) {
+                double d = fabs(clip_x(xi) - (*qmin + ((double)j + 0.5) * *qscale));
+                if (d < best) best = d;
+            }
+            near[i] = (uint8_t)(best <= band);
+        }
+    }
+    return 0;
+}
+
+/* Backward pass: Eq. 9 with the stored (min, scale), then Eq. 12, then the product. */
+int s2a_oracle_bwd_dyn(const void *dy, int dtype, const uint8_t *packed, int64_t n, double qmin,
+                       double qscale, double *dx)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n < 0) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        int q = (packed[i / 2] >> (4 * (i & 1))) & 0xF;
+        double xhat = s2a_oracle_dequantize_dyn(q, qmin, qscale);
+        dx[i] = load_elem(dy, dtype, i) * s2a_oracle_gelu_deriv_approx(xhat);
+    }
+    return 0;
+}
