@@ -12,7 +12,7 @@
  *   - Returns an int: S2A_OK (0) or a negative S2A_ERR_* value.  Nothing
  *     throws, nothing blocks: kernels are enqueued on `stream` and the call
  *     returns.  Argument errors are detected on the host before any device
- *     work, in the order NOT_INIT, DTYPE, SIZE, NULL.
+ *     work, in the order NOT_INIT, DTYPE, SIZE, NULL, ALIGN.
  *   - x, y, dy, dx and codes are DEVICE pointers owned by the caller.  The
  *     library allocates no device memory and keeps no reference to them.
  *   - Tensors are flat and contiguous; only the element count n matters.
@@ -46,8 +46,12 @@ enum {
     S2A_ERR_DTYPE = -3,    /* dtype is not an s2a_dtype */
     S2A_ERR_LEVELS = -4,   /* s2a_qtable_init: levels != 16 */
     S2A_ERR_NOT_INIT = -5, /* s2a_qtable_init has not succeeded yet */
-    S2A_ERR_LAUNCH = -6    /* the HIP runtime refused the launch */
+    S2A_ERR_LAUNCH = -6,   /* the HIP runtime refused the launch */
+    S2A_ERR_ALIGN = -7     /* qstate is not 4-byte aligned */
 };
+
+/* Floats of device memory behind a `qstate` pointer (see s2a_act_fwd_dyn). */
+#define S2A_QSTATE_FLOATS 32
 
 /*
  * Quantization-table setup (GeLU paragraph: x is clipped to [-2, 2] and
@@ -99,6 +103,32 @@ int s2a_act_fwd(const void* x, void* y, uint8_t* codes, int64_t n, int dtype, vo
  */
 int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int dtype,
                 void* stream);
+
+/*
+ * Measured-range variant (GeLU paragraph read literally: after the clip, x is
+ * "quantized between the maximal and minimal value" as in Eq. 8, i.e. min and
+ * max are those of the clipped tensor; Eq. 9 then needs the same pair in the
+ * backward pass).  One (min, scale) pair per call, kept beside the codes:
+ *
+ *   lo = min clip(x), hi = max clip(x), scale = (hi - lo) / 15
+ *   code[i] = round((clip(x[i]) - lo) / scale)          (all 0 when hi == lo)
+ *   dx[i]   = dy[i] * (sigma(1.702 xh) + 0.22 sin(1.5 xh)),  xh = code[i]*scale + lo
+ *
+ *   qstate  device, S2A_QSTATE_FLOATS floats, 4-byte aligned, caller-owned.
+ *           Forward overwrites all of it; backward only reads it.  Contents:
+ *           [2] = lo, [3] = scale, [16..31] = the 16 derivative levels; the
+ *           other entries are working values of the kernels.  NaN inputs clip
+ *           to -2 and take part in the minimum.  n == 0 leaves lo = scale = 0.
+ *
+ * Forward enqueues four kernels on `stream` (reset, min/max, finalize, the
+ * forward kernel proper) and reads x twice; everything else is as for
+ * s2a_act_fwd / s2a_act_bwd.  When the tensor has elements beyond both clip
+ * limits the results equal the fixed-range entry points'.
+ */
+int s2a_act_fwd_dyn(const void* x, void* y, uint8_t* codes, float* qstate, int64_t n, int dtype,
+                    void* stream);
+int s2a_act_bwd_dyn(const void* dy, const uint8_t* codes, const float* qstate, void* dx, int64_t n,
+                    int dtype, void* stream);
 
 /* Static, NUL-terminated description of a return code.  Never NULL. */
 const char* s2a_strerror(int code);

@@ -54,41 +54,85 @@ unsigned pair_grid(int64_t n)
     return (unsigned)(blocks < cap ? blocks : cap);
 }
 
-template <bool BF16>
-int launch_fwd(const void* x, void* y, uint8_t* codes, int64_t n, hipStream_t st)
+// Runs `launch` and turns the runtime's verdict into a return code.  Any stale
+// error left by earlier, unrelated runtime calls is dropped first.
+template <typename F>
+int checked_launch(F launch)
 {
-    constexpr int EPV = BF16 ? 8 : 4;
-    (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
-    if (aligned(x, 16) && aligned(y, 16) && aligned(codes, 4)) {
-        int64_t nvec = n / EPV;
-        int64_t slots = nvec + (n % EPV != 0);
-        int64_t blocks = (slots + s2a::kWave - 1) / s2a::kWave;
-        if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
-        s2a::fwd_kernel<BF16><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(
-            (const s2a::u32x4*)x, (s2a::u32x4*)y, codes, n, nvec);
-    } else {
-        s2a::fwd_kernel_unaligned<BF16><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(x, y, codes, n);
-    }
+    (void)hipGetLastError();
+    launch();
     return hipGetLastError() == hipSuccess ? S2A_OK : S2A_ERR_LAUNCH;
 }
 
+// Blocks of the vector kernels: one wave per 64 vectors (plus one slot for the leftover elements).
 template <bool BF16>
-int launch_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, hipStream_t st)
+bool vector_grid(int64_t n, int64_t* nvec, unsigned* blocks)
 {
     constexpr int EPV = BF16 ? 8 : 4;
-    (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
-    if (aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 4)) {
-        int64_t nvec = n / EPV;
-        int64_t slots = nvec + (n % EPV != 0);
-        int64_t blocks = (slots + s2a::kWave - 1) / s2a::kWave;
-        if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
-        s2a::bwd_kernel<BF16><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(
-            (const s2a::u32x4*)dy, codes, (s2a::u32x4*)dx, g_table.dev, n, nvec);
-    } else {
-        s2a::bwd_kernel_unaligned<BF16><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(
-            dy, codes, dx, g_table.dev, n);
+    *nvec = n / EPV;
+    int64_t slots = *nvec + (n % EPV != 0);
+    int64_t b = (slots + s2a::kWave - 1) / s2a::kWave;
+    if (b > 0x7fffffffLL) return false;
+    *blocks = (unsigned)b;
+    return true;
+}
+
+template <bool BF16, bool DYN>
+int launch_fwd(const void* x, void* y, uint8_t* codes, const float* qs, int64_t n, hipStream_t st)
+{
+    if (aligned(x, 16) && aligned(y, 16) && aligned(codes, 4)) {
+        int64_t nvec;
+        unsigned blocks;
+        if (!vector_grid<BF16>(n, &nvec, &blocks)) return S2A_ERR_SIZE;
+        return checked_launch([&] {
+            s2a::fwd_kernel<BF16, DYN><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+                (const s2a::u32x4*)x, (s2a::u32x4*)y, codes, qs, n, nvec);
+        });
     }
-    return hipGetLastError() == hipSuccess ? S2A_OK : S2A_ERR_LAUNCH;
+    return checked_launch([&] {
+        s2a::fwd_kernel_unaligned<BF16, DYN><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(x, y, codes, qs, n);
+    });
+}
+
+template <bool BF16, bool DYN>
+int launch_bwd(const void* dy, const uint8_t* codes, void* dx, const float* qs, int64_t n,
+               hipStream_t st)
+{
+    if (aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 4)) {
+        int64_t nvec;
+        unsigned blocks;
+        if (!vector_grid<BF16>(n, &nvec, &blocks)) return S2A_ERR_SIZE;
+        return checked_launch([&] {
+            s2a::bwd_kernel<BF16, DYN><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+                (const s2a::u32x4*)dy, codes, (s2a::u32x4*)dx, g_table.dev, qs, n, nvec);
+        });
+    }
+    return checked_launch([&] {
+        s2a::bwd_kernel_unaligned<BF16, DYN><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(
+            dy, codes, dx, g_table.dev, qs, n);
+    });
+}
+
+// The three small launches that measure the range of x and prepare qstate.
+template <bool BF16>
+int launch_range(const void* x, float* qs, int64_t n, hipStream_t st)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    int rc = checked_launch([&] { s2a::range_reset_kernel<<<dim3(1), dim3(1), 0, st>>>(qs); });
+    if (rc != S2A_OK) return rc;
+    const bool al = aligned(x, 16);
+    int64_t items = al ? n / EPV + 1 : n;
+    int64_t blocks = (items + s2a::kBlock - 1) / s2a::kBlock;
+    const int64_t cap = 256 * 8;  // 8 blocks of 256 lanes per CU; grid-stride beyond
+    if (blocks > cap) blocks = cap;
+    rc = checked_launch([&] {
+        if (al)
+            s2a::range_minmax_kernel<BF16, true><<<dim3((unsigned)blocks), dim3(s2a::kBlock), 0, st>>>(x, qs, n);
+        else
+            s2a::range_minmax_kernel<BF16, false><<<dim3((unsigned)blocks), dim3(s2a::kBlock), 0, st>>>(x, qs, n);
+    });
+    if (rc != S2A_OK) return rc;
+    return checked_launch([&] { s2a::range_finalize_kernel<<<dim3(1), dim3(s2a::kWave), 0, st>>>(qs); });
 }
 
 }  // namespace
@@ -119,8 +163,8 @@ int s2a_act_fwd(const void* x, void* y, uint8_t* codes, int64_t n, int dtype, vo
     int rc = check_common(x, y, codes, n, dtype);
     if (rc != S2A_OK || n == 0) return rc;
     hipStream_t st = (hipStream_t)stream;
-    return dtype == S2A_BF16 ? launch_fwd<true>(x, y, codes, n, st)
-                             : launch_fwd<false>(x, y, codes, n, st);
+    return dtype == S2A_BF16 ? launch_fwd<true, false>(x, y, codes, nullptr, n, st)
+                             : launch_fwd<false, false>(x, y, codes, nullptr, n, st);
 }
 
 int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int dtype, void* stream)
@@ -128,8 +172,36 @@ int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int d
     int rc = check_common(dy, codes, dx, n, dtype);
     if (rc != S2A_OK || n == 0) return rc;
     hipStream_t st = (hipStream_t)stream;
-    return dtype == S2A_BF16 ? launch_bwd<true>(dy, codes, dx, n, st)
-                             : launch_bwd<false>(dy, codes, dx, n, st);
+    return dtype == S2A_BF16 ? launch_bwd<true, false>(dy, codes, dx, nullptr, n, st)
+                             : launch_bwd<false, false>(dy, codes, dx, nullptr, n, st);
+}
+
+int s2a_act_fwd_dyn(const void* x, void* y, uint8_t* codes, float* qstate, int64_t n, int dtype,
+                    void* stream)
+{
+    int rc = check_common(x, y, codes, n, dtype);
+    if (rc != S2A_OK) return rc;
+    if (!qstate) return S2A_ERR_NULL;
+    if (((uintptr_t)qstate & 3u) != 0) return S2A_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    // n == 0 still leaves a defined state behind: min = max = 0, scale 0
+    rc = dtype == S2A_BF16 ? launch_range<true>(x, qstate, n, st) : launch_range<false>(x, qstate, n, st);
+    if (rc != S2A_OK || n == 0) return rc;
+    return dtype == S2A_BF16 ? launch_fwd<true, true>(x, y, codes, qstate, n, st)
+                             : launch_fwd<false, true>(x, y, codes, qstate, n, st);
+}
+
+int s2a_act_bwd_dyn(const void* dy, const uint8_t* codes, const float* qstate, void* dx, int64_t n,
+                    int dtype, void* stream)
+{
+    int rc = check_common(dy, codes, dx, n, dtype);
+    if (rc != S2A_OK) return rc;
+    if (!qstate) return S2A_ERR_NULL;
+    if (((uintptr_t)qstate & 3u) != 0) return S2A_ERR_ALIGN;
+    if (n == 0) return S2A_OK;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_bwd<true, true>(dy, codes, dx, qstate, n, st)
+                             : launch_bwd<false, true>(dy, codes, dx, qstate, n, st);
 }
 
 const char* s2a_strerror(int code)
@@ -142,6 +214,7 @@ const char* s2a_strerror(int code)
         case S2A_ERR_LEVELS: return "only 16 quantization levels (4-bit codes) are supported";
         case S2A_ERR_NOT_INIT: return "s2a_qtable_init has not been called";
         case S2A_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        case S2A_ERR_ALIGN: return "qstate is not 4-byte aligned";
         default: return "unknown s2a error code";
     }
 }

@@ -93,22 +93,34 @@ __device__ __forceinline__ float gelu_accurate(float x)
 
 // ------------------------------------------------------- clip + Eq. 8 ------
 
-// code = round((clip(x,-2,2) + 2) * 15/4).  Rounding to nearest equals
-// floor(3.75 xc + 8) because the only exact tie of the real-valued expression
-// is x = 0 (7.5 -> 8 under ties-to-even, and floor(8) = 8).  One FMA rounds the
-// exact value once.  The clip is applied after the conversion instead of
+// code = round((clip(x, lo, hi) - lo) * 15 / (hi - lo)) as one FMA and one
+// convert: t = x * scale + offset with scale = 15/(hi-lo), offset = 1/2 - lo*scale.
+// Rounding to nearest equals floor(t) because an exact tie of the real-valued
+// expression is itself a decision point (for the fixed range [-2, 2] the only
+// one is x = 0: 7.5 -> 8 under ties-to-even, and floor(8) = 8).  One FMA rounds
+// the exact value once.  The clip is applied after the conversion instead of
 // before it: v_cvt_u32_f32 truncates toward zero (the floor, for t >= 0) and
 // saturates -- negative and NaN inputs give 0, huge ones 0xffffffff -- so
 // min(c, 15) finishes the clip and NaN lands on code 0 like a value below the
 // range.  The instruction is written out because a C float-to-unsigned cast
 // leaves exactly those out-of-range cases undefined.
-__device__ __forceinline__ uint32_t bin16(float x)
+__device__ __forceinline__ uint32_t bin_affine(float x, float scale, float offset)
 {
-    float t = __builtin_fmaf(x, 3.75f, 8.0f);
+    float t = __builtin_fmaf(x, scale, offset);
     uint32_t c;
     asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));
     return c < 15u ? c : 15u;
 }
+
+// Fixed range: lo = -2, hi = 2 (the clip limits), scale = 3.75, offset = 8.
+struct BinFixed {
+    __device__ __forceinline__ uint32_t operator()(float x) const { return bin_affine(x, 3.75f, 8.0f); }
+};
+// Measured range: scale and offset prepared by range_finalize_kernel.
+struct BinRange {
+    float scale, offset;
+    __device__ __forceinline__ uint32_t operator()(float x) const { return bin_affine(x, scale, offset); }
+};
 
 // Shift a 4-bit code into the top of `acc`; after 8 pushes the first code
 // sits in bits 0..3.  (v_alignbit_b32: one op, no masking needed.)
@@ -197,61 +209,62 @@ __device__ __forceinline__ void store_codes(uint8_t* codes, int64_t v, uint32_t 
 // ------------------------------------------------- element-wise pieces ----
 
 // Elements [first, n) with first even: one code byte per pair, pad nibble 0.
-template <bool BF16>
-__device__ __forceinline__ void fwd_pairs(const void* x, void* y, uint8_t* codes, int64_t first,
-                                          int64_t n, int64_t pair0, int64_t pair_stride)
+template <bool BF16, typename Bin>
+__device__ __forceinline__ void fwd_pairs(const void* x, void* y, uint8_t* codes, Bin bin,
+                                          int64_t first, int64_t n, int64_t pair0,
+                                          int64_t pair_stride)
 {
     int64_t npairs = (n - first + 1) / 2;
     for (int64_t p = pair0; p < npairs; p += pair_stride) {
         int64_t i = first + 2 * p;
         float a = load_elem<BF16>(x, i);
-        uint32_t byte = bin16(a);
+        uint32_t byte = bin(a);
         store_elem<BF16>(y, i, gelu<BF16>(a));
         if (i + 1 < n) {
             float b = load_elem<BF16>(x, i + 1);
-            byte |= bin16(b) << 4;
+            byte |= bin(b) << 4;
             store_elem<BF16>(y, i + 1, gelu<BF16>(b));
         }
         codes[i / 2] = (uint8_t)byte;
     }
 }
 
-// `tab` is anything indexable by a code: an LDS array, or the by-value kernel
-// argument itself (the compiler then reads the kernarg segment).
-template <bool BF16, typename Tab>
+// `D` maps a code to its derivative level (an LDS array, the kernel arguments
+// or device memory behind it).
+template <bool BF16, typename Lookup>
 __device__ __forceinline__ void bwd_pairs(const void* dy, const uint8_t* codes, void* dx,
-                                          const Tab& tab, int64_t first, int64_t n,
+                                          Lookup D, int64_t first, int64_t n,
                                           int64_t pair0, int64_t pair_stride)
 {
     int64_t npairs = (n - first + 1) / 2;
     for (int64_t p = pair0; p < npairs; p += pair_stride) {
         int64_t i = first + 2 * p;
         uint32_t byte = codes[i / 2];
-        store_elem<BF16>(dx, i, load_elem<BF16>(dy, i) * tab[byte & 15u]);
-        if (i + 1 < n) store_elem<BF16>(dx, i + 1, load_elem<BF16>(dy, i + 1) * tab[byte >> 4]);
+        store_elem<BF16>(dx, i, load_elem<BF16>(dy, i) * D(byte & 15u));
+        if (i + 1 < n) store_elem<BF16>(dx, i + 1, load_elem<BF16>(dy, i + 1) * D(byte >> 4));
     }
 }
 
 // ------------------------------------------------------------- forward ----
 
 // One vector of 8 bf16: y bits in place, returns the 8 packed codes.
-template <bool BF16>
-__device__ __forceinline__ uint32_t fwd_vector(u32x4& v)
+template <bool BF16, typename Bin>
+__device__ __forceinline__ uint32_t fwd_vector(u32x4& v, Bin bin)
 {
     uint32_t acc = 0;
     if (BF16) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float a = bf16_lo(v[j]), b = bf16_hi(v[j]);
-            acc = push_nibble(acc, bin16(a));
-            acc = push_nibble(acc, bin16(b));
+            acc = push_nibble(acc, bin(a));
+            acc = push_nibble(acc, bin(b));
             v[j] = pack_bf16(gelu_fast(a), gelu_fast(b));
         }
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float a = as_f32(v[j]);
-            acc = push_nibble(acc, bin16(a));
+            acc = push_nibble(acc, bin(a));
             v[j] = as_u32(gelu_accurate(a));
         }
         acc >>= 16;  // 4 codes -> low 16 bits
@@ -259,35 +272,164 @@ __device__ __forceinline__ uint32_t fwd_vector(u32x4& v)
     return acc;
 }
 
+// Layout of the per-tensor quantizer state of the measured-range variant
+// (32 floats of caller-owned device memory, written by the forward pass and
+// read by the backward pass):
+//   [0], [1]  running minimum / maximum of clip(x), as order-preserving uint32
+//   [2] min   [3] scale = (max-min)/15   [4] 15/(max-min) (0 if max == min)
+//   [5] 1/2 - min * [4]                  [16..31] D[k] = Eq. 12 at min + k*scale
+constexpr int kQsMinBits = 0, kQsMaxBits = 1, kQsMin = 2, kQsScale = 3, kQsInv = 4, kQsOff = 5,
+              kQsTable = 16;
+
 // Vector kernel.  Requires x, y 16-byte aligned and codes 4-byte aligned.
 // x and y may be the same buffer (a lane loads its vector before it stores
 // it), so neither is declared restrict.
+//   DYN    false: fixed range [-2, 2]; true: range read from qs (see above)
 //   nvec   number of full vectors, n / EPV
 //   grid   ceil((nvec + (n % EPV != 0)) / kWave) blocks of kWave lanes
-template <bool BF16>
+template <bool BF16, bool DYN>
 __global__ __launch_bounds__(kWave) void fwd_kernel(const u32x4* x, u32x4* y,
-                                                    uint8_t* __restrict__ codes, int64_t n,
+                                                    uint8_t* __restrict__ codes,
+                                                    const float* __restrict__ qs, int64_t n,
                                                     int64_t nvec)
 {
     constexpr int EPV = BF16 ? 8 : 4;
+    typedef typename std::conditional<DYN, BinRange, BinFixed>::type Bin;
+    Bin bin;
+    if constexpr (DYN) bin = BinRange{qs[kQsInv], qs[kQsOff]};
     const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
     if (i < nvec) {
         u32x4 v = stream_load128(x + i);
-        uint32_t c = fwd_vector<BF16>(v);
+        uint32_t c = fwd_vector<BF16>(v, bin);
         stream_store128(y + i, v);
         store_codes<BF16>(codes, i, c);
     } else if (i == nvec) {  // one lane finishes the n % EPV leftover elements
-        fwd_pairs<BF16>(x, y, codes, nvec * EPV, n, 0, 1);
+        fwd_pairs<BF16>(x, y, codes, bin, nvec * EPV, n, 0, 1);
     }
 }
 
 // Any alignment: one lane per code byte, grid-stride.
-template <bool BF16>
+template <bool BF16, bool DYN>
 __global__ __launch_bounds__(kBlock) void fwd_kernel_unaligned(const void* x, void* y,
-                                                               uint8_t* codes, int64_t n)
+                                                               uint8_t* codes,
+                                                               const float* __restrict__ qs,
+                                                               int64_t n)
 {
-    fwd_pairs<BF16>(x, y, codes, 0, n, (int64_t)blockIdx.x * kBlock + threadIdx.x,
+    typedef typename std::conditional<DYN, BinRange, BinFixed>::type Bin;
+    Bin bin;
+    if constexpr (DYN) bin = BinRange{qs[kQsInv], qs[kQsOff]};
+    fwd_pairs<BF16>(x, y, codes, bin, 0, n, (int64_t)blockIdx.x * kBlock + threadIdx.x,
                     (int64_t)gridDim.x * kBlock);
+}
+
+// --------------------------------------------- measured range (Eq. 8) -----
+
+// Order-preserving map float -> uint32 (so that integer atomics order floats).
+__device__ __forceinline__ uint32_t float_to_ordered(float f)
+{
+    uint32_t u = as_u32(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_to_float(uint32_t u)
+{
+    return as_f32((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
+}
+// clip(x, -2, 2) with NaN -> -2 (a value below the range), as in the forward binning.
+__device__ __forceinline__ float clip_for_range(float x)
+{
+    return (x != x) ? -2.0f : __builtin_amdgcn_fmed3f(x, -2.0f, 2.0f);
+}
+
+__global__ void range_reset_kernel(float* qs)
+{
+    ((uint32_t*)qs)[kQsMinBits] = 0xffffffffu;
+    ((uint32_t*)qs)[kQsMaxBits] = 0u;
+}
+
+// min / max of clip(x) over the tensor: grid-stride over 16-byte vectors (or
+// over elements when ALIGNED is false), wave reduction by cross-lane shuffles,
+// block reduction through LDS, one pair of atomics per block.  The loads are
+// ordinary cached loads on purpose: a tensor that fits the 256 MB on-die cache
+// is then still there when the forward kernel reads it again.
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(kBlock) void range_minmax_kernel(const void* x, float* qs, int64_t n)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+    const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t nthreads = (int64_t)gridDim.x * kBlock;
+    int64_t done = 0;
+    if (ALIGNED) {
+        const int64_t nvec = n / EPV;
+        const u32x4* xv = (const u32x4*)x;
+        for (int64_t i = tid; i < nvec; i += nthreads) {
+            u32x4 v = xv[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (BF16) {
+                    float a = clip_for_range(bf16_lo(v[j])), b = clip_for_range(bf16_hi(v[j]));
+                    lo = fminf(lo, fminf(a, b));
+                    hi = fmaxf(hi, fmaxf(a, b));
+                } else {
+                    float a = clip_for_range(as_f32(v[j]));
+                    lo = fminf(lo, a);
+                    hi = fmaxf(hi, a);
+                }
+            }
+        }
+        done = nvec * EPV;
+    }
+    for (int64_t i = done + tid; i < n; i += nthreads) {  // leftover (or all) elements, one by one
+        float a = clip_for_range(load_elem<BF16>(x, i));
+        lo = fminf(lo, a);
+        hi = fmaxf(hi, a);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off, kWave));
+        hi = fmaxf(hi, __shfl_xor(hi, off, kWave));
+    }
+    __shared__ float slo[kBlock / kWave], shi[kBlock / kWave];
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        slo[threadIdx.x / kWave] = lo;
+        shi[threadIdx.x / kWave] = hi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kBlock / kWave; ++w) {
+            lo = fminf(lo, slo[w]);
+            hi = fmaxf(hi, shi[w]);
+        }
+        if (lo <= hi) {  // this block saw at least one element
+            atomicMin((uint32_t*)qs + kQsMinBits, float_to_ordered(lo));
+            atomicMax((uint32_t*)qs + kQsMaxBits, float_to_ordered(hi));
+        }
+    }
+}
+
+// One wave: turn (min, max) into scale, the binning constants and the 16
+// derivative levels D[k] = sigma(1.702 xhat_k) + 0.22 sin(1.5 xhat_k),
+// xhat_k = min + k * scale (Eq. 9, Eq. 12), all in double, rounded once.
+__global__ __launch_bounds__(kWave) void range_finalize_kernel(float* qs)
+{
+    const uint32_t lo_bits = ((const uint32_t*)qs)[kQsMinBits];
+    const bool empty = lo_bits == 0xffffffffu;  // still the reset value: the tensor had no elements
+    const double lo = empty ? 0.0 : (double)ordered_to_float(lo_bits);
+    const double hi = empty ? 0.0 : (double)ordered_to_float(((const uint32_t*)qs)[kQsMaxBits]);
+    const double scale = (hi - lo) / 15.0;
+    const int k = threadIdx.x;
+    if (k < 16) {
+        double xh = lo + scale * (double)k;
+        qs[kQsTable + k] = (float)(1.0 / (1.0 + exp(-1.702 * xh)) + 0.22 * sin(1.5 * xh));
+    }
+    if (k == 0) {
+        double inv = scale > 0.0 ? 1.0 / scale : 0.0;
+        qs[kQsMin] = (float)lo;
+        qs[kQsScale] = (float)scale;
+        qs[kQsInv] = (float)inv;
+        qs[kQsOff] = (float)(0.5 - lo * inv);
+    }
 }
 
 // ------------------------------------------------------------ backward ----
@@ -318,41 +460,46 @@ __device__ __forceinline__ void bwd_vector(u32x4& v, uint32_t c, Lookup D)
 }
 
 // Vector kernel of the backward pass; same layout and grid as fwd_kernel.
-// dy and dx may be the same buffer.
-template <bool BF16>
+// dy and dx may be the same buffer.  DYN selects the table: the fixed-range
+// levels passed by value, or the 16 levels the forward pass left in qs.
+template <bool BF16, bool DYN>
 __global__ __launch_bounds__(kWave) void bwd_kernel(const u32x4* dy,
                                                     const uint8_t* __restrict__ codes, u32x4* dx,
-                                                    QTable qt, int64_t n, int64_t nvec)
+                                                    QTable qt, const float* __restrict__ qs,
+                                                    int64_t n, int64_t nvec)
 {
     constexpr int EPV = BF16 ? 8 : 4;
     const int64_t wave0 = (int64_t)blockIdx.x * kWave;
     const int64_t i = wave0 + threadIdx.x;
+    auto level = [&](uint32_t code) { return DYN ? qs[kQsTable + code] : qt.d[code]; };
     if (wave0 + kWave <= nvec) {  // whole wave in range (a scalar branch): permute lookup
-        const int tv = __builtin_bit_cast(int, qt.d[threadIdx.x & 15]);
+        const int tv = __builtin_bit_cast(int, level(threadIdx.x & 15));
         u32x4 v = stream_load128(dy + i);
         uint32_t c = load_codes<BF16>(codes, i);
         bwd_vector<BF16>(v, c, [tv](uint32_t code) { return lookup_lane(code, tv); });
         stream_store128(dx + i, v);
-    } else if (i < nvec) {        // last, partial wave: read the table from the kernel arguments
+    } else if (i < nvec) {        // last, partial wave: read the table from memory
         u32x4 v = dy[i];
         uint32_t c = load_codes<BF16>(codes, i);
-        bwd_vector<BF16>(v, c, [&qt](uint32_t code) { return qt.d[code]; });
+        bwd_vector<BF16>(v, c, level);
         stream_store128(dx + i, v);
     } else if (i == nvec) {
-        bwd_pairs<BF16>(dy, codes, dx, qt.d, nvec * EPV, n, 0, 1);
+        bwd_pairs<BF16>(dy, codes, dx, level, nvec * EPV, n, 0, 1);
     }
 }
 
-template <bool BF16>
+template <bool BF16, bool DYN>
 __global__ __launch_bounds__(kBlock) void bwd_kernel_unaligned(const void* dy,
                                                                const uint8_t* codes, void* dx,
-                                                               QTable qt, int64_t n)
+                                                               QTable qt,
+                                                               const float* __restrict__ qs,
+                                                               int64_t n)
 {
     __shared__ float tab[16];
-    if (threadIdx.x < 16) tab[threadIdx.x] = qt.d[threadIdx.x];
+    if (threadIdx.x < 16) tab[threadIdx.x] = DYN ? qs[kQsTable + threadIdx.x] : qt.d[threadIdx.x];
     __syncthreads();
-    bwd_pairs<BF16>(dy, codes, dx, tab, 0, n, (int64_t)blockIdx.x * kBlock + threadIdx.x,
-                    (int64_t)gridDim.x * kBlock);
+    bwd_pairs<BF16>(dy, codes, dx, [&](uint32_t code) { return tab[code]; }, 0, n,
+                    (int64_t)blockIdx.x * kBlock + threadIdx.x, (int64_t)gridDim.x * kBlock);
 }
 
 }  // namespace s2a

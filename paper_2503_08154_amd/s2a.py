@@ -21,8 +21,11 @@ ERR_DTYPE = -3
 ERR_LEVELS = -4
 ERR_NOT_INIT = -5
 ERR_LAUNCH = -6
+ERR_ALIGN = -7
+QSTATE_FLOATS = 32
 
-EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd", "s2a_strerror")
+EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd",
+           "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_strerror")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libs2a.so")
 _lib = None
@@ -52,6 +55,10 @@ def lib() -> ctypes.CDLL:
         l.s2a_act_fwd.argtypes = [vp, vp, vp, i64, i, vp]
         l.s2a_act_bwd.restype = i
         l.s2a_act_bwd.argtypes = [vp, vp, vp, i64, i, vp]
+        l.s2a_act_fwd_dyn.restype = i
+        l.s2a_act_fwd_dyn.argtypes = [vp, vp, vp, vp, i64, i, vp]
+        l.s2a_act_bwd_dyn.restype = i
+        l.s2a_act_bwd_dyn.argtypes = [vp, vp, vp, vp, i64, i, vp]
         l.s2a_strerror.restype = ctypes.c_char_p
         l.s2a_strerror.argtypes = [i]
         _lib = l
@@ -91,4 +98,20 @@ def act_bwd(dy: int, codes: int, dx: int, n: int, dtype: int, stream: int = 0, c
     rc = lib().s2a_act_bwd(dy, codes, dx, int(n), int(dtype), stream)
     if check and rc != OK:
         raise S2AError(rc, "s2a_act_bwd")
+    return rc
+
+
+def act_fwd_dyn(x: int, y: int, codes: int, qstate: int, n: int, dtype: int, stream: int = 0,
+                check: bool = True) -> int:
+    rc = lib().s2a_act_fwd_dyn(x, y, codes, qstate, int(n), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_act_fwd_dyn")
+    return rc
+
+
+def act_bwd_dyn(dy: int, codes: int, qstate: int, dx: int, n: int, dtype: int, stream: int = 0,
+                check: bool = True) -> int:
+    rc = lib().s2a_act_bwd_dyn(dy, codes, qstate, dx, int(n), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_act_bwd_dyn")
     return rc

@@ -50,15 +50,26 @@ def test_error_paths_need_no_gpu():
         assert fn(None, None, None, 0, s2a.F32, check=False) == s2a.OK  # n == 0: nothing to do
     with pytest.raises(s2a.S2AError):
         s2a.act_fwd(None, fake, fake, 8, s2a.BF16)
+    # measured-range entry points: same checks, plus the state buffer
+    odd = ctypes.c_void_p(0x1002)
+    assert s2a.act_fwd_dyn(fake, fake, fake, fake, 8, 7, check=False) == s2a.ERR_DTYPE
+    assert s2a.act_fwd_dyn(fake, fake, fake, fake, -5, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.act_fwd_dyn(fake, None, fake, fake, 8, s2a.F32, check=False) == s2a.ERR_NULL
+    assert s2a.act_fwd_dyn(fake, fake, fake, None, 8, s2a.F32, check=False) == s2a.ERR_NULL
+    assert s2a.act_fwd_dyn(fake, fake, fake, odd, 8, s2a.F32, check=False) == s2a.ERR_ALIGN
+    assert s2a.act_bwd_dyn(fake, fake, fake, fake, 8, 7, check=False) == s2a.ERR_DTYPE
+    assert s2a.act_bwd_dyn(fake, fake, None, fake, 8, s2a.BF16, check=False) == s2a.ERR_NULL
+    assert s2a.act_bwd_dyn(fake, fake, odd, fake, 8, s2a.BF16, check=False) == s2a.ERR_ALIGN
+    assert s2a.act_bwd_dyn(None, None, fake, None, 0, s2a.BF16, check=False) == s2a.OK
 
 
 def test_strerror_is_total():
     seen = set()
-    for code in range(-8, 2):
+    for code in range(-9, 2):
         msg = s2a.strerror(code)
         assert isinstance(msg, str) and msg
         seen.add(msg)
-    assert len(seen) >= 8  # 7 known codes + "unknown"
+    assert len(seen) >= 9  # 8 known codes + "unknown"
 
 
 def test_table_matches_oracle_to_fp32_rounding():

@@ -1,0 +1,165 @@
+"""GPU parity of the measured-range variant (s2a_act_fwd_dyn / s2a_act_bwd_dyn)
+against the oracle: range, derivative levels, codes, y and dx."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_08154_amd import s2a
+from paper_2503_08154_amd import workloads as wl
+
+import gpu_util as gu
+import parity
+
+pytestmark = pytest.mark.gpu
+DTYPES = [wl.F32, wl.BF16]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _init():
+    assert torch.cuda.is_available()
+    s2a.qtable_init(16)
+
+
+def _draw(n, kind, dtype, seed):
+    g = np.random.Generator(np.random.Philox(seed))
+    if kind == "narrow":          # never reaches a clip limit: the range is really measured
+        a = g.uniform(-1.3, 0.9, n)
+    elif kind == "small":         # N(0, 0.3^2), clipped tails absent
+        a = np.clip(g.standard_normal(n) * 0.3, -1.9, 1.9)
+    elif kind == "one_sided":     # reaches the upper limit only
+        a = np.abs(g.standard_normal(n)) * 1.5 + 0.25
+    elif kind == "wide":          # reaches both limits: equals the fixed-range variant
+        a = g.standard_normal(n) * 1.5
+    else:
+        raise ValueError(kind)
+    return wl.to_storage(a, dtype)
+
+
+def _run_dyn(x, dy, dtype, offset_elems=0, code_offset=0, packed_for_bwd=None):
+    n = x.shape[0]
+    es = gu.esize(dtype)
+    bx = gu.Buf(n * es, offset_elems * es).upload(x)
+    by = gu.Buf(n * es, offset_elems * es)
+    bc = gu.Buf((n + 1) // 2, code_offset)
+    bq = gu.Buf(4 * s2a.QSTATE_FLOATS)
+    st = torch.cuda.current_stream().cuda_stream
+    s2a.act_fwd_dyn(bx.ptr, by.ptr, bc.ptr, bq.ptr, n, dtype, st)
+    torch.cuda.synchronize()
+    assert by.canaries_intact() and bc.canaries_intact() and bq.canaries_intact() and bx.canaries_intact()
+    y = by.download(gu.storage_np(dtype))
+    packed = bc.download(np.uint8)
+    qs = bq.download(np.float32)
+    bdy = gu.Buf(n * es, offset_elems * es).upload(dy)
+    bdx = gu.Buf(n * es, offset_elems * es)
+    outs = []
+    for pk in ([packed] if packed_for_bwd is None else [packed, packed_for_bwd]):
+        bc2 = gu.Buf((n + 1) // 2, code_offset).upload(pk)
+        s2a.act_bwd_dyn(bdy.ptr, bc2.ptr, bq.ptr, bdx.ptr, n, dtype, st)
+        torch.cuda.synchronize()
+        assert bdx.canaries_intact()
+        outs.append(bdx.download(gu.storage_np(dtype)))
+    return y, packed, qs, outs
+
+
+def _check(x, dy, dtype, **kw):
+    n = x.shape[0]
+    y_ref, code_ref, packed_ref, near, qmin, qscale = oracle.fwd_dyn(x, dtype, band=parity.BAND)
+    y, packed, qs, dxs = _run_dyn(x, dy, dtype, packed_for_bwd=packed_ref, **kw)
+    # range and derivative levels: the oracle's doubles, rounded once to fp32
+    assert qs[2] == np.float32(qmin) and qs[3] == np.float32(qscale)
+    levels = np.array([oracle.gelu_deriv_approx(oracle.dequantize_dyn(k, qmin, qscale)) for k in range(16)])
+    np.testing.assert_allclose(qs[16:32].astype(np.float64), levels, rtol=2e-7, atol=1e-12)
+    finite = np.isfinite(wl.storage_to_f64(x, dtype))
+    rep = parity.check_codes(packed, code_ref, near, n)
+    wy = parity.check_values(y, y_ref, dtype, "y", finite_in=finite)
+    dx_ref = oracle.bwd_dyn(dy, dtype, packed_ref, qmin, qscale)
+    wdx = parity.check_values(dxs[1], dx_ref, dtype, "dx")          # oracle's codes in: every element
+    differs = parity.unpack(packed, n) != code_ref
+    parity.check_values(dxs[0], dx_ref, dtype, "dx", skip=differs)  # the GPU's own codes
+    return rep, wy, wdx, qs
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind", ["narrow", "small", "one_sided", "wide"])
+@pytest.mark.parametrize("n", [1, 2, 3, 9, 64, 257, 513, 4097, 8192 * 3 + 5, 302592, 2_000_003])
+def test_sizes_and_ranges(dtype, kind, n):
+    x = _draw(n, kind, dtype, seed=100 + n)
+    dy = wl.draw_dy(n, 1.0, dtype, seed=200 + n)
+    _check(x, dy, dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("off", [(1, 0), (0, 1), (3, 3)])
+def test_unaligned(dtype, off):
+    n = 8192 * 2 + 3
+    x = _draw(n, "narrow", dtype, seed=7)
+    dy = wl.draw_dy(n, 1e-2, dtype, seed=8)
+    _check(x, dy, dtype, offset_elems=off[0], code_offset=off[1])
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_equals_fixed_range_when_both_limits_are_reached(dtype):
+    n = 302592
+    x = _draw(n, "wide", dtype, seed=11)
+    dy = wl.draw_dy(n, 1e-2, dtype, seed=12)
+    _, packed_dyn, qs, dxs = _run_dyn(x, dy, dtype)
+    y_fix, packed_fix = gu.run_fwd(x, dtype)
+    np.testing.assert_array_equal(packed_dyn, packed_fix)
+    assert qs[2] == -2.0 and qs[3] == np.float32(4.0 / 15.0)
+    _, deriv, _ = s2a.qtable_get()
+    np.testing.assert_array_equal(qs[16:32], np.array(deriv, np.float32))
+    np.testing.assert_array_equal(dxs[0].view(np.uint8), gu.run_bwd(dy, packed_fix, dtype).view(np.uint8))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_degenerate_tensors(dtype):
+    dy = wl.to_storage(np.array([2.0, -1.0, 0.5, 3.0, 1.0, 1.0, 1.0]), dtype)
+    # all equal -> scale 0, codes 0, every level equals Eq. 12 at the value
+    x = wl.to_storage(np.full(7, 0.75), dtype)
+    rep, _, _, qs = _check(x, dy, dtype)
+    assert qs[2] == 0.75 and qs[3] == 0.0
+    # everything beyond the upper clip limit
+    x = wl.to_storage(np.array([5.0, 7.0, 1e30, np.inf, 2.5, 3.0, 9.0]), dtype)
+    _, _, _, qs = _check(x, dy, dtype)
+    assert qs[2] == 2.0 and qs[3] == 0.0
+    # a NaN clips to -2: it sets the minimum and gets code 0
+    x = wl.to_storage(np.array([0.5, np.nan, 1.0, 0.75, 0.6, 0.9, 0.55]), dtype)
+    _, _, _, qs = _check(x, dy, dtype)
+    assert qs[2] == -2.0
+    # n == 0: a defined, empty state
+    bq = gu.Buf(4 * s2a.QSTATE_FLOATS)
+    s2a.act_fwd_dyn(None, None, None, bq.ptr, 0, dtype, torch.cuda.current_stream().cuda_stream)
+    qs = bq.download(np.float32)
+    assert qs[2] == 0.0 and qs[3] == 0.0 and bq.canaries_intact()
+
+
+@pytest.mark.parametrize("name", ["vit_b16", "vit_g14_f32"])
+def test_workload_full_size(name):
+    """Full-size launch; the activations are scaled down so that no element reaches a
+    clip limit and the measured range differs from [-2, 2]."""
+    w = wl.WORKLOADS[name]
+    n = w.sizes()[0]
+    g = np.random.Generator(np.random.Philox(wl.layer_seed(w, 0, 0, "x")))
+    x = wl.to_storage(np.clip(g.standard_normal(n) * 0.35, -1.75, 1.9), w.dtype)
+    dy = wl.draw_dy(n, w.dy_scale, w.dtype, wl.layer_seed(w, 0, 0, "dy"))
+    st = torch.cuda.current_stream().cuda_stream
+    tx = torch.from_numpy(x.view(np.uint8)).cuda()
+    ty = torch.empty_like(tx)
+    tc = torch.empty((n + 1) // 2, dtype=torch.uint8, device="cuda")
+    tq = torch.empty(s2a.QSTATE_FLOATS, dtype=torch.float32, device="cuda")
+    s2a.act_fwd_dyn(tx.data_ptr(), ty.data_ptr(), tc.data_ptr(), tq.data_ptr(), n, w.dtype, st)
+    tdy = torch.from_numpy(dy.view(np.uint8)).cuda()
+    tdx = torch.empty_like(tdy)
+    s2a.act_bwd_dyn(tdy.data_ptr(), tc.data_ptr(), tq.data_ptr(), tdx.data_ptr(), n, w.dtype, st)
+    torch.cuda.synchronize()
+    y_ref, code_ref, packed_ref, near, qmin, qscale = oracle.fwd_dyn(x, w.dtype, band=parity.BAND)
+    qs = tq.cpu().numpy()
+    assert qs[2] == np.float32(qmin) and qs[3] == np.float32(qscale) and qmin > -2.0
+    packed = tc.cpu().numpy()
+    rep = parity.check_codes(packed, code_ref, near, n)
+    wy = parity.check_values(ty.cpu().numpy().view(gu.storage_np(w.dtype)), y_ref, w.dtype, "y")
+    dx_ref = oracle.bwd_dyn(dy, w.dtype, packed_ref, qmin, qscale)
+    differs = parity.unpack(packed, n) != code_ref
+    wdx = parity.check_values(tdx.cpu().numpy().view(gu.storage_np(w.dtype)), dx_ref, w.dtype, "dx", skip=differs)
+    print(f"\n[dyn {name}] n={n} range=[{qmin:.4f}, {qmin + 15 * qscale:.4f}] {rep} worst y {wy:.3f} worst dx {wdx:.3f}")
