@@ -65,7 +65,8 @@ class Layer:
         self.y = torch.empty_like(self.x)
         self.dx = torch.empty_like(self.dy)
         self.codes = torch.empty((self.n + 1) // 2, dtype=torch.uint8, device="cuda")
-        self.p = tuple(t.data_ptr() for t in (self.x, self.y, self.codes, self.dy, self.dx))
+        self.qstate = torch.empty(s2a.QSTATE_FLOATS, dtype=torch.float32, device="cuda")
+        self.p = tuple(t.data_ptr() for t in (self.x, self.y, self.codes, self.dy, self.dx, self.qstate))
 
 
 def build_layers(torch, w: wl.Workload, distinct_seeds: bool):
@@ -80,30 +81,37 @@ def build_layers(torch, w: wl.Workload, distinct_seeds: bool):
     return [Layer(torch, x, dy, w.dtype) for (x, dy) in host]
 
 
-def run_step(layers, stream: int, ev=None):
-    """fwd over all layers, then bwd in reverse; optional (e0, e1, e2) events around the phases."""
+def run_step(layers, stream: int, ev=None, dyn: bool = False):
+    """fwd over all layers, then bwd in reverse; optional (e0, e1, e2) events around the phases.
+    dyn selects the measured-range entry points."""
     if ev:
         ev[0].record()
     for L in layers:
-        s2a.act_fwd(L.p[0], L.p[1], L.p[2], L.n, L.dtype, stream)
+        if dyn:
+            s2a.act_fwd_dyn(L.p[0], L.p[1], L.p[2], L.p[5], L.n, L.dtype, stream)
+        else:
+            s2a.act_fwd(L.p[0], L.p[1], L.p[2], L.n, L.dtype, stream)
     if ev:
         ev[1].record()
     for L in reversed(layers):
-        s2a.act_bwd(L.p[3], L.p[2], L.p[4], L.n, L.dtype, stream)
+        if dyn:
+            s2a.act_bwd_dyn(L.p[3], L.p[2], L.p[5], L.p[4], L.n, L.dtype, stream)
+        else:
+            s2a.act_bwd(L.p[3], L.p[2], L.p[4], L.n, L.dtype, stream)
     if ev:
         ev[2].record()
 
 
-def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds: bool):
+def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds: bool, dyn: bool = False):
     layers = build_layers(torch, w, distinct_seeds)
     stream = torch.cuda.current_stream().cuda_stream
     for _ in range(warmup):
-        run_step(layers, stream)
+        run_step(layers, stream, dyn=dyn)
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
-        run_step(layers, stream, events[k])
+        run_step(layers, stream, events[k], dyn=dyn)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in events)
@@ -259,6 +267,19 @@ def main():
                 "buffer_sets": tw.layers, "slower": rf["kernel"],
             }
         out["target_shapes"] = targets
+        # next row: the measured-range quantizer (Eq. 8 read literally).  Its forward reads x twice
+        # (range pass, then the forward kernel), so its algorithmic bytes are 3e + 0.5 per element.
+        tw = wl.WORKLOADS["vit_l16"]
+        r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False, dyn=True)
+        n1 = tw.sizes()[0]
+        fwd_bytes = (3 * esize(tw.dtype) + 0.5) * n1
+        out["measured_range_variant"] = {
+            "workload": "vit_l16", "fwd_us": round(r["fwd_us_per_launch"], 2), "bwd_us": round(r["bwd_us_per_launch"], 2),
+            "fwd_gbs": round(fwd_bytes / r["fwd_us_per_launch"] / 1e3, 1),
+            "fwd_frac": round(fwd_bytes / r["fwd_us_per_launch"] / 1e3 / HBM_PEAK_GBS, 4),
+            "bwd_gbs": round(r["bwd_gbs"], 1), "bwd_frac": round(r["bwd_gbs"] / HBM_PEAK_GBS, 4),
+            "fwd_algorithmic_bytes_per_launch": fwd_bytes,
+        }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -51,7 +51,7 @@ enum {
 };
 
 /* Floats of device memory behind a `qstate` pointer (see s2a_act_fwd_dyn). */
-#define S2A_QSTATE_FLOATS 32
+#define S2A_QSTATE_FLOATS 544
 
 /*
  * Quantization-table setup (GeLU paragraph: x is clipped to [-2, 2] and
@@ -115,13 +115,17 @@ int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int d
  *   dx[i]   = dy[i] * (sigma(1.702 xh) + 0.22 sin(1.5 xh)),  xh = code[i]*scale + lo
  *
  *   qstate  device, S2A_QSTATE_FLOATS floats, 4-byte aligned, caller-owned.
- *           Forward overwrites all of it; backward only reads it.  Contents:
- *           [2] = lo, [3] = scale, [16..31] = the 16 derivative levels; the
- *           other entries are working values of the kernels.  NaN inputs clip
- *           to -2 and take part in the minimum.  n == 0 leaves lo = scale = 0.
+ *           Forward overwrites it and needs no initialisation; backward only
+ *           reads entries 16..31.  Contents: [2] = lo, [3] = scale, [16..31] =
+ *           the 16 derivative levels; the other entries are working values of
+ *           the kernels (binning constants, per-block minima and maxima).  NaN
+ *           inputs clip to -2 and take part in the minimum.  n == 0 leaves
+ *           lo = scale = 0.
  *
- * Forward enqueues four kernels on `stream` (reset, min/max, finalize, the
- * forward kernel proper) and reads x twice; everything else is as for
+ * Forward enqueues three kernels on `stream` (per-block min/max, the reduction
+ * of those to the range and the levels, the forward kernel proper) and reads x
+ * twice; no atomics are used, so the result does not depend on scheduling.
+ * Everything else is as for
  * s2a_act_fwd / s2a_act_bwd.  When the tensor has elements beyond both clip
  * limits the results equal the fixed-range entry points'.
  */

@@ -113,27 +113,29 @@ int launch_bwd(const void* dy, const uint8_t* codes, void* dx, const float* qs, 
     });
 }
 
-// The three small launches that measure the range of x and prepare qstate.
+// The two launches that measure the range of x and prepare qstate.
 template <bool BF16>
 int launch_range(const void* x, float* qs, int64_t n, hipStream_t st)
 {
     constexpr int EPV = BF16 ? 8 : 4;
-    int rc = checked_launch([&] { s2a::range_reset_kernel<<<dim3(1), dim3(1), 0, st>>>(qs); });
-    if (rc != S2A_OK) return rc;
     const bool al = aligned(x, 16);
     int64_t items = al ? n / EPV + 1 : n;
-    int64_t blocks = (items + s2a::kBlock - 1) / s2a::kBlock;
-    const int64_t cap = 256 * 8;  // 8 blocks of 256 lanes per CU; grid-stride beyond
-    if (blocks > cap) blocks = cap;
-    rc = checked_launch([&] {
+    int64_t blocks = (items + s2a::kRangeBlock - 1) / s2a::kRangeBlock;
+    if (blocks > s2a::kRangeBlocks) blocks = s2a::kRangeBlocks;  // grid-stride beyond
+    if (blocks < 1) blocks = 1;
+    int rc = checked_launch([&] {
         if (al)
-            s2a::range_minmax_kernel<BF16, true><<<dim3((unsigned)blocks), dim3(s2a::kBlock), 0, st>>>(x, qs, n);
+            s2a::range_minmax_kernel<BF16, true><<<dim3((unsigned)blocks), dim3(s2a::kRangeBlock), 0, st>>>(x, qs, n);
         else
-            s2a::range_minmax_kernel<BF16, false><<<dim3((unsigned)blocks), dim3(s2a::kBlock), 0, st>>>(x, qs, n);
+            s2a::range_minmax_kernel<BF16, false><<<dim3((unsigned)blocks), dim3(s2a::kRangeBlock), 0, st>>>(x, qs, n);
     });
     if (rc != S2A_OK) return rc;
-    return checked_launch([&] { s2a::range_finalize_kernel<<<dim3(1), dim3(s2a::kWave), 0, st>>>(qs); });
+    return checked_launch([&] {
+        s2a::range_finalize_kernel<<<dim3(1), dim3(s2a::kRangeBlock), 0, st>>>(qs, (int)blocks);
+    });
 }
+
+static_assert(s2a::kQsFloats == S2A_QSTATE_FLOATS, "header and kernels disagree on the qstate size");
 
 }  // namespace
 

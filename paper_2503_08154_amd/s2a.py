@@ -22,7 +22,7 @@ ERR_LEVELS = -4
 ERR_NOT_INIT = -5
 ERR_LAUNCH = -6
 ERR_ALIGN = -7
-QSTATE_FLOATS = 32
+QSTATE_FLOATS = 544
 
 EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd",
            "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_strerror")
