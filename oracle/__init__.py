@@ -57,6 +57,10 @@ def _load():
         lib.s2a_oracle_fwd.argtypes = [vp, i, i64, vp, vp, vp, vp, d]
         lib.s2a_oracle_bwd.restype = i
         lib.s2a_oracle_bwd.argtypes = [vp, i, vp, i64, vp]
+        lib.s2a_oracle_relu_fwd.restype = i
+        lib.s2a_oracle_relu_fwd.argtypes = [vp, i, i64, vp, vp, vp]
+        lib.s2a_oracle_relu_bwd.restype = i
+        lib.s2a_oracle_relu_bwd.argtypes = [vp, i, vp, i64, vp]
         lib.s2a_oracle_range.restype = i
         lib.s2a_oracle_range.argtypes = [vp, i, i64, vp, vp]
         lib.s2a_oracle_quantize_dyn.restype = i
@@ -185,4 +189,29 @@ def bwd_dyn(dy: np.ndarray, dtype: int, packed: np.ndarray, qmin: float, qscale:
                                     float(qscale), dx.ctypes.data)
     if rc != 0:
         raise ValueError("s2a_oracle_bwd_dyn rejected its arguments")
+    return dx
+
+
+# ---- ReLU 1-bit mask ----
+
+def relu_fwd(x: np.ndarray, dtype: int):
+    """Returns (y float64[n], bit uint8[n], packed uint8[(n+7)//8])."""
+    x = _storage(x, dtype)
+    n = x.shape[0]
+    y = np.empty(n, np.float64)
+    bit = np.empty(n, np.uint8)
+    packed = np.empty((n + 7) // 8, np.uint8)
+    if _load().s2a_oracle_relu_fwd(x.ctypes.data, dtype, n, y.ctypes.data, bit.ctypes.data, packed.ctypes.data) != 0:
+        raise ValueError("s2a_oracle_relu_fwd rejected its arguments")
+    return y, bit, packed
+
+
+def relu_bwd(dy: np.ndarray, dtype: int, packed: np.ndarray) -> np.ndarray:
+    dy = _storage(dy, dtype)
+    n = dy.shape[0]
+    if packed.dtype != np.uint8 or packed.shape != ((n + 7) // 8,) or not packed.flags.c_contiguous:
+        raise TypeError("packed must be contiguous uint8 of length ceil(n/8)")
+    dx = np.empty(n, np.float64)
+    if _load().s2a_oracle_relu_bwd(dy.ctypes.data, dtype, packed.ctypes.data, n, dx.ctypes.data) != 0:
+        raise ValueError("s2a_oracle_relu_bwd rejected its arguments")
     return dx

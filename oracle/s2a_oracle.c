@@ -260,3 +260,40 @@ int s2a_oracle_bwd_dyn(const void *dy, int dtype, const uint8_t *packed, int64_t
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * ReLU layer (Sec. 3.2, "ReLU layer" paragraph): the derivative takes the two
+ * values 0 and 1, so the saved activation is the 1-bit mask "x > 0".
+ *
+ * Readings: the mask is strict (x = 0 has derivative 0, as in PyTorch); y is
+ * x where the mask is set and +0 elsewhere (NaN has no order, so NaN -> 0);
+ * eight mask bits per byte, element 8j+b in bit b of byte j, pad bits 0.
+ *
+ * Pins (tests/test_oracle_relu_pins.py): y against a library ReLU, the mask
+ * against numpy's little-endian bit packing of (x > 0), the backward pass
+ * against automatic differentiation of a library ReLU, the 32x size ratio.
+ * ---------------------------------------------------------------------- */
+int s2a_oracle_relu_fwd(const void *x, int dtype, int64_t n, double *y, uint8_t *bit,
+                        uint8_t *packed)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n < 0) return -1;
+    if (packed) memset(packed, 0, (size_t)((n + 7) / 8));
+    for (int64_t i = 0; i < n; ++i) {
+        double xi = load_elem(x, dtype, i);
+        int m = xi > 0.0;
+        if (y) y[i] = m ? xi : 0.0;
+        if (bit) bit[i] = (uint8_t)m;
+        if (packed) packed[i / 8] |= (uint8_t)(m << (i & 7));
+    }
+    return 0;
+}
+
+int s2a_oracle_relu_bwd(const void *dy, int dtype, const uint8_t *packed, int64_t n, double *dx)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n < 0) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        int m = (packed[i / 8] >> (i & 7)) & 1;
+        dx[i] = m ? load_elem(dy, dtype, i) : 0.0;
+    }
+    return 0;
+}
