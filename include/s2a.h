@@ -134,6 +134,19 @@ int s2a_act_fwd_dyn(const void* x, void* y, uint8_t* codes, float* qstate, int64
 int s2a_act_bwd_dyn(const void* dy, const uint8_t* codes, const float* qstate, void* dx, int64_t n,
                     int dtype, void* stream);
 
+/*
+ * ReLU with a 1-bit saved activation (Sec. 3.2, "ReLU layer": the derivative
+ * is 0 or 1, so the mask x > 0 is all the backward pass needs).
+ *   forward   y[i] = x[i] > 0 ? x[i] : 0;  bit i of `mask` = x[i] > 0
+ *   backward  dx[i] = bit i ? dy[i] : 0
+ * `mask` holds ceil(n/8) bytes, element 8j+b in bit b of byte j, pad bits 0.
+ * The mask is strict (x = 0 and NaN give bit 0 and y = 0).  Needs no
+ * s2a_qtable_init.  x/y/dy/dx 16-byte aligned take the vector kernels; y == x
+ * and dx == dy are allowed.
+ */
+int s2a_relu_fwd(const void* x, void* y, uint8_t* mask, int64_t n, int dtype, void* stream);
+int s2a_relu_bwd(const void* dy, const uint8_t* mask, void* dx, int64_t n, int dtype, void* stream);
+
 /* Static, NUL-terminated description of a return code.  Never NULL. */
 const char* s2a_strerror(int code);
 

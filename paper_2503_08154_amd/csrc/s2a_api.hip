@@ -34,6 +34,14 @@ void build_table(TableState& t)
     t.ready = true;
 }
 
+int check_args(const void* a, const void* b, const void* c, int64_t n, int dtype)
+{
+    if (dtype != S2A_F32 && dtype != S2A_BF16) return S2A_ERR_DTYPE;
+    if (n < 0) return S2A_ERR_SIZE;
+    if (n > 0 && (!a || !b || !c)) return S2A_ERR_NULL;
+    return S2A_OK;
+}
+
 int check_common(const void* a, const void* b, const void* c, int64_t n, int dtype)
 {
     if (!g_table.ready) return S2A_ERR_NOT_INIT;
@@ -135,6 +143,40 @@ int launch_range(const void* x, float* qs, int64_t n, hipStream_t st)
     });
 }
 
+template <bool BF16>
+int launch_relu_fwd(const void* x, void* y, uint8_t* mask, int64_t n, hipStream_t st)
+{
+    if (aligned(x, 16) && aligned(y, 16)) {
+        int64_t nvec;
+        unsigned blocks;
+        if (!vector_grid<BF16>(n, &nvec, &blocks)) return S2A_ERR_SIZE;
+        return checked_launch([&] {
+            s2a::relu_fwd_kernel<BF16><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+                (const s2a::u32x4*)x, (s2a::u32x4*)y, mask, n, nvec);
+        });
+    }
+    return checked_launch([&] {
+        s2a::relu_fwd_kernel_unaligned<BF16><<<dim3(pair_grid(n / 4 + 1)), dim3(s2a::kBlock), 0, st>>>(x, y, mask, n);
+    });
+}
+
+template <bool BF16>
+int launch_relu_bwd(const void* dy, const uint8_t* mask, void* dx, int64_t n, hipStream_t st)
+{
+    if (aligned(dy, 16) && aligned(dx, 16)) {
+        int64_t nvec;
+        unsigned blocks;
+        if (!vector_grid<BF16>(n, &nvec, &blocks)) return S2A_ERR_SIZE;
+        return checked_launch([&] {
+            s2a::relu_bwd_kernel<BF16><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+                (const s2a::u32x4*)dy, mask, (s2a::u32x4*)dx, n, nvec);
+        });
+    }
+    return checked_launch([&] {
+        s2a::relu_bwd_kernel_unaligned<BF16><<<dim3(pair_grid(n / 4 + 1)), dim3(s2a::kBlock), 0, st>>>(dy, mask, dx, n);
+    });
+}
+
 static_assert(s2a::kQsFloats == S2A_QSTATE_FLOATS, "header and kernels disagree on the qstate size");
 
 }  // namespace
@@ -204,6 +246,24 @@ int s2a_act_bwd_dyn(const void* dy, const uint8_t* codes, const float* qstate, v
     hipStream_t st = (hipStream_t)stream;
     return dtype == S2A_BF16 ? launch_bwd<true, true>(dy, codes, dx, qstate, n, st)
                              : launch_bwd<false, true>(dy, codes, dx, qstate, n, st);
+}
+
+int s2a_relu_fwd(const void* x, void* y, uint8_t* mask, int64_t n, int dtype, void* stream)
+{
+    int rc = check_args(x, y, mask, n, dtype);
+    if (rc != S2A_OK || n == 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_relu_fwd<true>(x, y, mask, n, st)
+                             : launch_relu_fwd<false>(x, y, mask, n, st);
+}
+
+int s2a_relu_bwd(const void* dy, const uint8_t* mask, void* dx, int64_t n, int dtype, void* stream)
+{
+    int rc = check_args(dy, mask, dx, n, dtype);
+    if (rc != S2A_OK || n == 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_relu_bwd<true>(dy, mask, dx, n, st)
+                             : launch_relu_bwd<false>(dy, mask, dx, n, st);
 }
 
 const char* s2a_strerror(int code)

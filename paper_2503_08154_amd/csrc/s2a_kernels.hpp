@@ -528,4 +528,120 @@ __global__ __launch_bounds__(kBlock) void bwd_kernel_unaligned(const void* dy,
                     (int64_t)blockIdx.x * kBlock + threadIdx.x, (int64_t)gridDim.x * kBlock);
 }
 
+// ------------------------------------------------ ReLU 1-bit mask ---------
+//
+// Sec. 3.2, "ReLU layer": the derivative is 0 or 1, so the saved activation is
+// the mask x > 0, one bit per element (element 8j+b in bit b of byte j).
+//   forward   y = x > 0 ? x : 0,  bit = x > 0        (2e + 1/8 bytes per element)
+//   backward  dx = bit ? dy : 0                       (2e + 1/8 bytes per element)
+// Same streaming skeleton as the GELU kernels: single-wave blocks, one 16-byte
+// vector per lane.  A bf16 vector owns exactly one mask byte; an fp32 vector
+// owns a nibble, and the even lane of each lane pair fetches its neighbour's
+// nibble with a cross-lane shuffle and stores the byte.  The lane just past
+// the last full vector takes the n % EPV leftover elements, so that a byte is
+// still written by exactly one lane.
+
+__device__ __forceinline__ float relu(float x) { return x > 0.0f ? x : 0.0f; }
+
+template <bool BF16>
+__global__ __launch_bounds__(kWave) void relu_fwd_kernel(const u32x4* x, u32x4* y,
+                                                         uint8_t* __restrict__ mask, int64_t n,
+                                                         int64_t nvec)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    uint32_t bits = 0;
+    if (i < nvec) {
+        u32x4 v = stream_load128(x + i);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (BF16) {
+                // NaN compares false: bit 0, y = 0.  y keeps x's bits where the bit is set.
+                float a = bf16_lo(v[j]), b = bf16_hi(v[j]);
+                uint32_t ma = a > 0.0f, mb = b > 0.0f;
+                bits |= (ma << (2 * j)) | (mb << (2 * j + 1));
+                v[j] = (ma ? (v[j] & 0x0000ffffu) : 0u) | (mb ? (v[j] & 0xffff0000u) : 0u);
+            } else {
+                float a = as_f32(v[j]);
+                uint32_t ma = a > 0.0f;
+                bits |= ma << j;
+                v[j] = ma ? v[j] : 0u;
+            }
+        }
+        stream_store128(y + i, v);
+    } else if (i == nvec) {
+        for (int64_t e = nvec * EPV; e < n; ++e) {
+            float a = load_elem<BF16>(x, e);
+            bits |= (uint32_t)(a > 0.0f) << (e - nvec * EPV);
+            store_elem<BF16>(y, e, relu(a));
+        }
+    }
+    // every lane of the wave takes part in the shuffle
+    if (BF16) {
+        if (i * EPV < n) mask[i] = (uint8_t)bits;
+    } else {
+        uint32_t other = (uint32_t)__shfl_xor((int)bits, 1, kWave);
+        if ((threadIdx.x & 1) == 0 && i * EPV < n) mask[i >> 1] = (uint8_t)(bits | (other << 4));
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kWave) void relu_bwd_kernel(const u32x4* dy,
+                                                         const uint8_t* __restrict__ mask,
+                                                         u32x4* dx, int64_t n, int64_t nvec)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    if (i < nvec) {
+        u32x4 v = stream_load128(dy + i);
+        uint32_t bits = BF16 ? mask[i] : (uint32_t)(mask[i >> 1] >> (4 * (i & 1)));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (BF16)
+                v[j] &= (((bits >> (2 * j)) & 1u) ? 0x0000ffffu : 0u) |
+                        (((bits >> (2 * j + 1)) & 1u) ? 0xffff0000u : 0u);
+            else
+                v[j] = ((bits >> j) & 1u) ? v[j] : 0u;
+        }
+        stream_store128(dx + i, v);
+    } else if (i == nvec) {
+        for (int64_t e = nvec * EPV; e < n; ++e) {
+            uint32_t m = (mask[e >> 3] >> (e & 7)) & 1u;
+            store_elem<BF16>(dx, e, m ? load_elem<BF16>(dy, e) : 0.0f);
+        }
+    }
+}
+
+// Any alignment: one lane per mask byte (8 elements), grid-stride.
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void relu_fwd_kernel_unaligned(const void* x, void* y,
+                                                                    uint8_t* mask, int64_t n)
+{
+    const int64_t nbytes = (n + 7) / 8;
+    for (int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x; b < nbytes;
+         b += (int64_t)gridDim.x * kBlock) {
+        uint32_t bits = 0;
+        for (int k = 0; k < 8 && b * 8 + k < n; ++k) {
+            float a = load_elem<BF16>(x, b * 8 + k);
+            bits |= (uint32_t)(a > 0.0f) << k;
+            store_elem<BF16>(y, b * 8 + k, relu(a));
+        }
+        mask[b] = (uint8_t)bits;
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void relu_bwd_kernel_unaligned(const void* dy,
+                                                                    const uint8_t* mask, void* dx,
+                                                                    int64_t n)
+{
+    const int64_t nbytes = (n + 7) / 8;
+    for (int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x; b < nbytes;
+         b += (int64_t)gridDim.x * kBlock) {
+        uint32_t bits = mask[b];
+        for (int k = 0; k < 8 && b * 8 + k < n; ++k)
+            store_elem<BF16>(dx, b * 8 + k, ((bits >> k) & 1u) ? load_elem<BF16>(dy, b * 8 + k) : 0.0f);
+    }
+}
+
 }  // namespace s2a

@@ -25,7 +25,7 @@ ERR_ALIGN = -7
 QSTATE_FLOATS = 544
 
 EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd",
-           "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_strerror")
+           "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_relu_fwd", "s2a_relu_bwd", "s2a_strerror")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libs2a.so")
 _lib = None
@@ -59,6 +59,10 @@ def lib() -> ctypes.CDLL:
         l.s2a_act_fwd_dyn.argtypes = [vp, vp, vp, vp, i64, i, vp]
         l.s2a_act_bwd_dyn.restype = i
         l.s2a_act_bwd_dyn.argtypes = [vp, vp, vp, vp, i64, i, vp]
+        l.s2a_relu_fwd.restype = i
+        l.s2a_relu_fwd.argtypes = [vp, vp, vp, i64, i, vp]
+        l.s2a_relu_bwd.restype = i
+        l.s2a_relu_bwd.argtypes = [vp, vp, vp, i64, i, vp]
         l.s2a_strerror.restype = ctypes.c_char_p
         l.s2a_strerror.argtypes = [i]
         _lib = l
@@ -114,4 +118,18 @@ def act_bwd_dyn(dy: int, codes: int, qstate: int, dx: int, n: int, dtype: int, s
     rc = lib().s2a_act_bwd_dyn(dy, codes, qstate, dx, int(n), int(dtype), stream)
     if check and rc != OK:
         raise S2AError(rc, "s2a_act_bwd_dyn")
+    return rc
+
+
+def relu_fwd(x: int, y: int, mask: int, n: int, dtype: int, stream: int = 0, check: bool = True) -> int:
+    rc = lib().s2a_relu_fwd(x, y, mask, int(n), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_relu_fwd")
+    return rc
+
+
+def relu_bwd(dy: int, mask: int, dx: int, n: int, dtype: int, stream: int = 0, check: bool = True) -> int:
+    rc = lib().s2a_relu_bwd(dy, mask, dx, int(n), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_relu_bwd")
     return rc

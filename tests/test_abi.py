@@ -50,6 +50,12 @@ def test_error_paths_need_no_gpu():
         assert fn(None, None, None, 0, s2a.F32, check=False) == s2a.OK  # n == 0: nothing to do
     with pytest.raises(s2a.S2AError):
         s2a.act_fwd(None, fake, fake, 8, s2a.BF16)
+    # ReLU entry points need no table
+    for fn in (s2a.relu_fwd, s2a.relu_bwd):
+        assert fn(fake, fake, fake, 8, 3, check=False) == s2a.ERR_DTYPE
+        assert fn(fake, fake, fake, -2, s2a.F32, check=False) == s2a.ERR_SIZE
+        assert fn(fake, None, fake, 8, s2a.F32, check=False) == s2a.ERR_NULL
+        assert fn(None, None, None, 0, s2a.BF16, check=False) == s2a.OK
     # measured-range entry points: same checks, plus the state buffer
     odd = ctypes.c_void_p(0x1002)
     assert s2a.act_fwd_dyn(fake, fake, fake, fake, 8, 7, check=False) == s2a.ERR_DTYPE
