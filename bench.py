@@ -67,6 +67,7 @@ class Layer:
         self.codes = torch.empty((self.n + 1) // 2, dtype=torch.uint8, device="cuda")
         self.qstate = torch.empty(s2a.QSTATE_FLOATS, dtype=torch.float32, device="cuda")
         self.p = tuple(t.data_ptr() for t in (self.x, self.y, self.codes, self.dy, self.dx, self.qstate))
+        # the ReLU mask (n/8 bytes) fits in the codes buffer (n/2 bytes)
 
 
 def build_layers(torch, w: wl.Workload, distinct_seeds: bool):
@@ -81,37 +82,41 @@ def build_layers(torch, w: wl.Workload, distinct_seeds: bool):
     return [Layer(torch, x, dy, w.dtype) for (x, dy) in host]
 
 
-def run_step(layers, stream: int, ev=None, dyn: bool = False):
+def run_step(layers, stream: int, ev=None, variant: str = "gelu"):
     """fwd over all layers, then bwd in reverse; optional (e0, e1, e2) events around the phases.
-    dyn selects the measured-range entry points."""
+    variant: "gelu" (the headline path), "gelu_dyn" (measured range) or "relu" (1-bit mask)."""
     if ev:
         ev[0].record()
     for L in layers:
-        if dyn:
+        if variant == "gelu_dyn":
             s2a.act_fwd_dyn(L.p[0], L.p[1], L.p[2], L.p[5], L.n, L.dtype, stream)
+        elif variant == "relu":
+            s2a.relu_fwd(L.p[0], L.p[1], L.p[2], L.n, L.dtype, stream)
         else:
             s2a.act_fwd(L.p[0], L.p[1], L.p[2], L.n, L.dtype, stream)
     if ev:
         ev[1].record()
     for L in reversed(layers):
-        if dyn:
+        if variant == "gelu_dyn":
             s2a.act_bwd_dyn(L.p[3], L.p[2], L.p[5], L.p[4], L.n, L.dtype, stream)
+        elif variant == "relu":
+            s2a.relu_bwd(L.p[3], L.p[2], L.p[4], L.n, L.dtype, stream)
         else:
             s2a.act_bwd(L.p[3], L.p[2], L.p[4], L.n, L.dtype, stream)
     if ev:
         ev[2].record()
 
 
-def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds: bool, dyn: bool = False):
+def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds: bool, variant: str = "gelu"):
     layers = build_layers(torch, w, distinct_seeds)
     stream = torch.cuda.current_stream().cuda_stream
     for _ in range(warmup):
-        run_step(layers, stream, dyn=dyn)
+        run_step(layers, stream, variant=variant)
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
-        run_step(layers, stream, events[k], dyn=dyn)
+        run_step(layers, stream, events[k], variant=variant)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in events)
@@ -270,7 +275,7 @@ def main():
         # next row: the measured-range quantizer (Eq. 8 read literally).  Its forward reads x twice
         # (range pass, then the forward kernel), so its algorithmic bytes are 3e + 0.5 per element.
         tw = wl.WORKLOADS["vit_l16"]
-        r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False, dyn=True)
+        r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False, variant="gelu_dyn")
         n1 = tw.sizes()[0]
         fwd_bytes = (3 * esize(tw.dtype) + 0.5) * n1
         out["measured_range_variant"] = {
@@ -279,6 +284,17 @@ def main():
             "fwd_frac": round(fwd_bytes / r["fwd_us_per_launch"] / 1e3 / HBM_PEAK_GBS, 4),
             "bwd_gbs": round(r["bwd_gbs"], 1), "bwd_frac": round(r["bwd_gbs"] / HBM_PEAK_GBS, 4),
             "fwd_algorithmic_bytes_per_launch": fwd_bytes,
+        }
+        # next row: ReLU with a 1-bit mask; 2e + 1/8 bytes per element and direction
+        r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False, variant="relu")
+        relu_bytes = (2 * esize(tw.dtype) + 0.125) * n1
+        out["relu_mask"] = {
+            "workload": "vit_l16", "fwd_us": round(r["fwd_us_per_launch"], 2), "bwd_us": round(r["bwd_us_per_launch"], 2),
+            "fwd_gbs": round(relu_bytes / r["fwd_us_per_launch"] / 1e3, 1),
+            "fwd_frac": round(relu_bytes / r["fwd_us_per_launch"] / 1e3 / HBM_PEAK_GBS, 4),
+            "bwd_gbs": round(relu_bytes / r["bwd_us_per_launch"] / 1e3, 1),
+            "bwd_frac": round(relu_bytes / r["bwd_us_per_launch"] / 1e3 / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes_per_launch": relu_bytes,
         }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
