@@ -61,6 +61,10 @@ def _load():
         lib.s2a_oracle_relu_fwd.argtypes = [vp, i, i64, vp, vp, vp]
         lib.s2a_oracle_relu_bwd.restype = i
         lib.s2a_oracle_relu_bwd.argtypes = [vp, i, vp, i64, vp]
+        lib.s2a_oracle_softmax_fwd.restype = i
+        lib.s2a_oracle_softmax_fwd.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp, d]
+        lib.s2a_oracle_softmax_bwd.restype = i
+        lib.s2a_oracle_softmax_bwd.argtypes = [vp, i, vp, vp, vp, i64, i64, vp]
         lib.s2a_oracle_range.restype = i
         lib.s2a_oracle_range.argtypes = [vp, i, i64, vp, vp]
         lib.s2a_oracle_quantize_dyn.restype = i
@@ -214,4 +218,43 @@ def relu_bwd(dy: np.ndarray, dtype: int, packed: np.ndarray) -> np.ndarray:
     dx = np.empty(n, np.float64)
     if _load().s2a_oracle_relu_bwd(dy.ctypes.data, dtype, packed.ctypes.data, n, dx.ctypes.data) != 0:
         raise ValueError("s2a_oracle_relu_bwd rejected its arguments")
+    return dx
+
+
+# ---- Softmax with 4-bit y (Eq. 7-9) ----
+
+def softmax_fwd(x: np.ndarray, dtype: int, rows: int, L: int, band_t: float = 1e-4):
+    """x: storage array of rows*L elements.  Returns (y[rows*L], code[rows*L],
+    packed[rows*ceil(L/2)], qmin[rows], qscale[rows], near[rows*L])."""
+    x = _storage(x, dtype)
+    if x.shape[0] != rows * L:
+        raise ValueError("x must hold rows*L elements")
+    y = np.empty(rows * L, np.float64)
+    code = np.empty(rows * L, np.uint8)
+    packed = np.empty(rows * ((L + 1) // 2), np.uint8)
+    qmin = np.empty(rows, np.float64)
+    qscale = np.empty(rows, np.float64)
+    near = np.empty(rows * L, np.uint8)
+    rc = _load().s2a_oracle_softmax_fwd(x.ctypes.data, dtype, rows, L, y.ctypes.data, code.ctypes.data,
+                                        packed.ctypes.data, qmin.ctypes.data, qscale.ctypes.data,
+                                        near.ctypes.data, float(band_t))
+    if rc != 0:
+        raise ValueError("s2a_oracle_softmax_fwd rejected its arguments")
+    return y, code, packed, qmin, qscale, near
+
+
+def softmax_bwd(dy: np.ndarray, dtype: int, packed: np.ndarray, qmin: np.ndarray, qscale: np.ndarray,
+                rows: int, L: int) -> np.ndarray:
+    dy = _storage(dy, dtype)
+    if dy.shape[0] != rows * L or packed.shape != (rows * ((L + 1) // 2),) or packed.dtype != np.uint8:
+        raise ValueError("shape mismatch")
+    qmin = np.ascontiguousarray(qmin, np.float64)
+    qscale = np.ascontiguousarray(qscale, np.float64)
+    if qmin.shape != (rows,) or qscale.shape != (rows,):
+        raise ValueError("one (min, scale) pair per row")
+    dx = np.empty(rows * L, np.float64)
+    rc = _load().s2a_oracle_softmax_bwd(dy.ctypes.data, dtype, packed.ctypes.data, qmin.ctypes.data,
+                                        qscale.ctypes.data, rows, L, dx.ctypes.data)
+    if rc != 0:
+        raise ValueError("s2a_oracle_softmax_bwd rejected its arguments")
     return dx

@@ -297,3 +297,81 @@ int s2a_oracle_relu_bwd(const void *dy, int dtype, const uint8_t *packed, int64_
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Softmax layer (Sec. 3.2, "Softmax layer" paragraph, Eq. 7-9).  The gradient
+ * of softmax needs only y, and y lies in (0, 1) with sum 1, so y is what gets
+ * quantized: asymmetric N-bit quantization between its minimum and maximum
+ * (Eq. 8), dequantized by Eq. 9 before the gradient of Eq. 7 is formed.
+ *
+ * Layout: `rows` vectors of length L, contiguous (row stride L).  Codes are
+ * packed two per byte within a row, each row starting on a byte:
+ * ceil(L/2) bytes per row, element 2j in the low nibble, odd L leaves the last
+ * high nibble 0.  One (min, scale) pair per row.
+ *
+ * Readings: N = 4 as for GELU (Sec. 4.3 quantizes both to 4 bits); min and max
+ * are taken per softmax vector (Eq. 8 is written for the vector y); a row
+ * whose y are all equal has scale 0 and codes 0; the exponentials are taken
+ * relative to the row maximum, which is Eq. 7 in exact arithmetic and avoids
+ * overflow (so -inf inputs give y = 0); rounding is half-to-even.
+ *
+ * Pins (tests/test_oracle_softmax_pins.py): a library softmax; the literal
+ * quotient of Eq. 7; sum 1 and shift invariance; exact rational arithmetic for
+ * the codes; automatic differentiation of a library softmax on rows whose y sit
+ * exactly on the 16 levels; the closed forms for constant rows and for L = 2.
+ * ---------------------------------------------------------------------- */
+int s2a_oracle_softmax_fwd(const void *x, int dtype, int64_t rows, int64_t L, double *y,
+                           uint8_t *code, uint8_t *packed, double *qmin, double *qscale,
+                           uint8_t *near, double band_t)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || rows < 0 || L < 1) return -1;
+    const int64_t rb = (L + 1) / 2;
+    const double levels = (double)((1 << ORACLE_NBITS) - 1);
+    if (packed) memset(packed, 0, (size_t)(rows * rb));
+    for (int64_t r = 0; r < rows; ++r) {
+        double m = -INFINITY, sum = 0.0;
+        for (int64_t i = 0; i < L; ++i) m = fmax(m, load_elem(x, dtype, r * L + i));
+        for (int64_t i = 0; i < L; ++i) sum += exp(load_elem(x, dtype, r * L + i) - m);
+        double lo = INFINITY, hi = -INFINITY;
+        for (int64_t i = 0; i < L; ++i) {                       /* Eq. 7 */
+            double yi = exp(load_elem(x, dtype, r * L + i) - m) / sum;
+            y[r * L + i] = yi;
+            lo = fmin(lo, yi);
+            hi = fmax(hi, yi);
+        }
+        double s = (hi - lo) / levels;                          /* Eq. 8 */
+        if (qmin) qmin[r] = lo;
+        if (qscale) qscale[r] = s;
+        for (int64_t i = 0; i < L; ++i) {
+            double t = s > 0.0 ? (y[r * L + i] - lo) / s : 0.0;
+            int q = (int)nearbyint(t);
+            if (code) code[r * L + i] = (uint8_t)q;
+            if (packed) packed[r * rb + i / 2] |= (uint8_t)(q << (4 * (i & 1)));
+            if (near) near[r * L + i] = (uint8_t)(fabs(t - floor(t) - 0.5) <= band_t);
+        }
+    }
+    return 0;
+}
+
+/* Eq. 9, then the product of dL/dy with the Jacobian of Eq. 7 written with y-hat:
+ * dx_i = yh_i * (dy_i - sum_j yh_j dy_j). */
+int s2a_oracle_softmax_bwd(const void *dy, int dtype, const uint8_t *packed, const double *qmin,
+                           const double *qscale, int64_t rows, int64_t L, double *dx)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || rows < 0 || L < 1) return -1;
+    const int64_t rb = (L + 1) / 2;
+    for (int64_t r = 0; r < rows; ++r) {
+        double dot = 0.0;
+        for (int64_t i = 0; i < L; ++i) {
+            int q = (packed[r * rb + i / 2] >> (4 * (i & 1))) & 0xF;
+            double yh = (double)q * qscale[r] + qmin[r];
+            dot += yh * load_elem(dy, dtype, r * L + i);
+        }
+        for (int64_t i = 0; i < L; ++i) {
+            int q = (packed[r * rb + i / 2] >> (4 * (i & 1))) & 0xF;
+            double yh = (double)q * qscale[r] + qmin[r];
+            dx[r * L + i] = yh * (load_elem(dy, dtype, r * L + i) - dot);
+        }
+    }
+    return 0;
+}
