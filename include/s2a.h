@@ -47,7 +47,7 @@ enum {
     S2A_ERR_LEVELS = -4,   /* s2a_qtable_init: levels != 16 */
     S2A_ERR_NOT_INIT = -5, /* s2a_qtable_init has not succeeded yet */
     S2A_ERR_LAUNCH = -6,   /* the HIP runtime refused the launch */
-    S2A_ERR_ALIGN = -7     /* qstate is not 4-byte aligned */
+    S2A_ERR_ALIGN = -7     /* qstate / qparams is not 4-byte aligned */
 };
 
 /* Floats of device memory behind a `qstate` pointer (see s2a_act_fwd_dyn). */
@@ -146,6 +146,30 @@ int s2a_act_bwd_dyn(const void* dy, const uint8_t* codes, const float* qstate, v
  */
 int s2a_relu_fwd(const void* x, void* y, uint8_t* mask, int64_t n, int dtype, void* stream);
 int s2a_relu_bwd(const void* dy, const uint8_t* mask, void* dx, int64_t n, int dtype, void* stream);
+
+/*
+ * Softmax with a 4-bit saved output (Sec. 3.2, "Softmax layer", Eq. 7-9): the
+ * gradient of softmax needs only y, so y is quantized between its row minimum
+ * and maximum (Eq. 8, N = 4) and dequantized (Eq. 9) before the gradient.
+ *   forward   y = softmax(x) along rows of length L (Eq. 7)
+ *             lo = min y, s = (max y - min y)/15, code = round((y - lo)/s)
+ *   backward  yh = code*s + lo;  dx_i = yh_i * (dy_i - sum_j yh_j dy_j)
+ *
+ *   x, y, dy, dx  device, rows*L elements of `dtype`, row stride L (y may equal
+ *                 x, dx may equal dy)
+ *   codes         device, rows * ceil(L/2) bytes: every row starts on a byte,
+ *                 element 2j in the low nibble; odd L leaves the last high
+ *                 nibble 0
+ *   qparams       device, 2*rows floats, 4-byte aligned: (lo, s) of row r at
+ *                 [2r], [2r+1].  A row of equal y has s = 0 and codes 0.
+ *   L             1 <= L <= 1024 (else S2A_ERR_SIZE); rows >= 0
+ * Inputs of -inf (masked logits) give y = 0.  Needs no s2a_qtable_init.
+ */
+#define S2A_SOFTMAX_MAX_L 1024
+int s2a_softmax_fwd(const void* x, void* y, uint8_t* codes, float* qparams, int64_t rows, int64_t L,
+                    int dtype, void* stream);
+int s2a_softmax_bwd(const void* dy, const uint8_t* codes, const float* qparams, void* dx,
+                    int64_t rows, int64_t L, int dtype, void* stream);
 
 /* Static, NUL-terminated description of a return code.  Never NULL. */
 const char* s2a_strerror(int code);

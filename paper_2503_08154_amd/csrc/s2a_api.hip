@@ -177,6 +177,69 @@ int launch_relu_bwd(const void* dy, const uint8_t* mask, void* dx, int64_t n, hi
     });
 }
 
+// Lanes per softmax row: the smallest group whose lanes hold at most kSoftmaxSlots elements each.
+int softmax_group(int64_t L)
+{
+    for (int g = 8; g <= 64; g *= 2)
+        if ((L + g - 1) / g <= s2a::kSoftmaxSlots) return g;
+    return 0;
+}
+
+template <bool BF16, int G>
+int launch_softmax_fwd_g(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
+                         hipStream_t st)
+{
+    int64_t blocks = (rows + (s2a::kWave / G) - 1) / (s2a::kWave / G);
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    return checked_launch([&] {
+        s2a::softmax_fwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(x, y, codes, qp, rows, L);
+    });
+}
+template <bool BF16, int G>
+int launch_softmax_bwd_g(const void* dy, const uint8_t* codes, const float* qp, void* dx,
+                         int64_t rows, int L, hipStream_t st)
+{
+    int64_t blocks = (rows + (s2a::kWave / G) - 1) / (s2a::kWave / G);
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    return checked_launch([&] {
+        s2a::softmax_bwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(dy, codes, qp, dx, rows, L);
+    });
+}
+template <bool BF16>
+int launch_softmax_fwd(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
+                       hipStream_t st)
+{
+    switch (softmax_group(L)) {
+        case 8: return launch_softmax_fwd_g<BF16, 8>(x, y, codes, qp, rows, L, st);
+        case 16: return launch_softmax_fwd_g<BF16, 16>(x, y, codes, qp, rows, L, st);
+        case 32: return launch_softmax_fwd_g<BF16, 32>(x, y, codes, qp, rows, L, st);
+        case 64: return launch_softmax_fwd_g<BF16, 64>(x, y, codes, qp, rows, L, st);
+        default: return S2A_ERR_SIZE;
+    }
+}
+template <bool BF16>
+int launch_softmax_bwd(const void* dy, const uint8_t* codes, const float* qp, void* dx,
+                       int64_t rows, int L, hipStream_t st)
+{
+    switch (softmax_group(L)) {
+        case 8: return launch_softmax_bwd_g<BF16, 8>(dy, codes, qp, dx, rows, L, st);
+        case 16: return launch_softmax_bwd_g<BF16, 16>(dy, codes, qp, dx, rows, L, st);
+        case 32: return launch_softmax_bwd_g<BF16, 32>(dy, codes, qp, dx, rows, L, st);
+        case 64: return launch_softmax_bwd_g<BF16, 64>(dy, codes, qp, dx, rows, L, st);
+        default: return S2A_ERR_SIZE;
+    }
+}
+
+int check_softmax(const void* a, const void* b, const void* c, const void* d, int64_t rows,
+                  int64_t L, int dtype)
+{
+    if (dtype != S2A_F32 && dtype != S2A_BF16) return S2A_ERR_DTYPE;
+    if (rows < 0 || L < 1 || L > s2a::kSoftmaxMaxL) return S2A_ERR_SIZE;
+    if (rows > 0 && (!a || !b || !c || !d)) return S2A_ERR_NULL;
+    if (((uintptr_t)d & 3u) != 0) return S2A_ERR_ALIGN;
+    return S2A_OK;
+}
+
 static_assert(s2a::kQsFloats == S2A_QSTATE_FLOATS, "header and kernels disagree on the qstate size");
 
 }  // namespace
@@ -266,6 +329,26 @@ int s2a_relu_bwd(const void* dy, const uint8_t* mask, void* dx, int64_t n, int d
                              : launch_relu_bwd<false>(dy, mask, dx, n, st);
 }
 
+int s2a_softmax_fwd(const void* x, void* y, uint8_t* codes, float* qparams, int64_t rows, int64_t L,
+                    int dtype, void* stream)
+{
+    int rc = check_softmax(x, y, codes, qparams, rows, L, dtype);
+    if (rc != S2A_OK || rows == 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_softmax_fwd<true>(x, y, codes, qparams, rows, (int)L, st)
+                             : launch_softmax_fwd<false>(x, y, codes, qparams, rows, (int)L, st);
+}
+
+int s2a_softmax_bwd(const void* dy, const uint8_t* codes, const float* qparams, void* dx,
+                    int64_t rows, int64_t L, int dtype, void* stream)
+{
+    int rc = check_softmax(dy, codes, dx, qparams, rows, L, dtype);
+    if (rc != S2A_OK || rows == 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_softmax_bwd<true>(dy, codes, qparams, dx, rows, (int)L, st)
+                             : launch_softmax_bwd<false>(dy, codes, qparams, dx, rows, (int)L, st);
+}
+
 const char* s2a_strerror(int code)
 {
     switch (code) {
@@ -276,7 +359,7 @@ const char* s2a_strerror(int code)
         case S2A_ERR_LEVELS: return "only 16 quantization levels (4-bit codes) are supported";
         case S2A_ERR_NOT_INIT: return "s2a_qtable_init has not been called";
         case S2A_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
-        case S2A_ERR_ALIGN: return "qstate is not 4-byte aligned";
+        case S2A_ERR_ALIGN: return "qstate / qparams is not 4-byte aligned";
         default: return "unknown s2a error code";
     }
 }

@@ -644,4 +644,184 @@ __global__ __launch_bounds__(kBlock) void relu_bwd_kernel_unaligned(const void* 
     }
 }
 
+// ------------------------------------------ Softmax with 4-bit y ----------
+//
+// Sec. 3.2, "Softmax layer", Eq. 7-9.  Per row of length L:
+//   forward   y = softmax(x)                                       (Eq. 7)
+//             lo = min y, hi = max y, s = (hi - lo)/15
+//             code = round((y - lo)/s)                              (Eq. 8, N = 4)
+//             saved: codes (row-aligned, ceil(L/2) bytes) and (lo, s) per row
+//   backward  yh = code*s + lo                                      (Eq. 9)
+//             dx_i = yh_i * (dy_i - sum_j yh_j dy_j)               (Eq. 7's Jacobian)
+//
+// A row is handled by a group of G lanes (G = 8, 16, 32 or 64, the smallest with
+// ceil(L/G) <= 16), so a wave holds 64/G rows and all row reductions are
+// cross-lane shuffles inside the group: no LDS, no barrier.  Lane l of the
+// group owns elements l, l+G, l+2G, ...; since G is even, elements 2j and 2j+1
+// sit in neighbouring lanes at the same step, and the even lane packs both
+// codes into the byte it stores.
+constexpr int kSoftmaxSlots = 16;    // elements per lane at most
+constexpr int kSoftmaxMaxL = 64 * kSoftmaxSlots;
+
+template <int G>
+__device__ __forceinline__ float group_max(float v)
+{
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+template <int G>
+__device__ __forceinline__ float group_min(float v)
+{
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) v = fminf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+template <int G, typename T>
+__device__ __forceinline__ T group_sum(T v)
+{
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// exp(x - m) for x <= m.  The bf16 storage path takes the plain route.  The
+// fp32 storage path keeps 1e-6 relative accuracy down to the smallest results:
+// the difference x - m is formed exactly as s + err (two-sum), and the exponent
+// (s + err) * log2(e) as an exact hi + lo pair; otherwise the rounding of the
+// difference alone costs 2e-6 relative at x - m = -36.  Differences below -200
+// (e^-200 is 0 in fp32; this includes masked logits of -inf) return 0.
+template <bool BF16>
+__device__ __forceinline__ float exp_diff(float x, float m)
+{
+    constexpr double kL2e = 1.4426950408889634074;
+    constexpr float hi = (float)kL2e, lo = (float)(kL2e - (double)hi);
+    float s = x - m;
+    if (BF16) return __builtin_amdgcn_exp2f(fmaxf(s, -200.0f) * hi);
+    float bb = s - x;
+    float err = (x - (s - bb)) + (-m - bb);
+    const bool ok = s > -200.0f;  // false for -inf and NaN as well
+    s = ok ? s : -200.0f;
+    err = ok ? err : 0.0f;
+    float t = s * hi;
+    float tl = __builtin_fmaf(s, hi, -t);
+    tl = __builtin_fmaf(s, lo, tl);
+    tl = __builtin_fmaf(err, hi, tl);
+    return __builtin_amdgcn_exp2f(t) * __builtin_fmaf(tl, kLn2, 1.0f);
+}
+
+template <bool BF16, int G>
+__global__ __launch_bounds__(kWave) void softmax_fwd_kernel(const void* x, void* y,
+                                                            uint8_t* __restrict__ codes,
+                                                            float* __restrict__ qparams,
+                                                            int64_t rows, int L)
+{
+    constexpr int RPW = kWave / G;  // rows per wave
+    const int l = threadIdx.x % G;
+    const int64_t row = (int64_t)blockIdx.x * RPW + threadIdx.x / G;
+    const bool live = row < rows;
+    const int64_t base = row * L;
+    const float ninf = -__builtin_inff();
+
+    float v[kSoftmaxSlots];
+    float m = ninf;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots; ++k) {
+        v[k] = ninf;
+        if (k * G < L) {  // uniform over the wave
+            const int idx = l + k * G;
+            if (live && idx < L) v[k] = load_elem<BF16>(x, base + idx);
+            m = fmaxf(m, v[k]);
+        }
+    }
+    m = group_max<G>(m);
+
+    // the fp32 storage path sums in double: 197 fp32 additions could otherwise eat the 1e-6 budget
+    typedef typename std::conditional<BF16, float, double>::type acc_t;
+    acc_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots; ++k)
+        if (k * G < L) {
+            v[k] = exp_diff<BF16>(v[k], m);  // slots past the row end hold -inf -> 0
+            sum += (acc_t)v[k];
+        }
+    sum = group_sum<G>(sum);
+    const float inv = (float)((acc_t)1 / sum);
+
+    float lo = __builtin_inff(), hi = ninf;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots; ++k)
+        if (k * G < L) {
+            const int idx = l + k * G;
+            v[k] *= inv;
+            if (idx < L) {
+                lo = fminf(lo, v[k]);
+                hi = fmaxf(hi, v[k]);
+                if (live) store_elem<BF16>(y, base + idx, v[k]);
+            }
+        }
+    lo = group_min<G>(lo);
+    hi = group_max<G>(hi);
+    const float scale = (hi - lo) / 15.0f;
+    const float inv_scale = scale > 0.0f ? 15.0f / (hi - lo) : 0.0f;
+    if (live && l == 0) {
+        qparams[2 * row] = lo;
+        qparams[2 * row + 1] = scale;
+    }
+    const int64_t cbase = row * ((L + 1) / 2);
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots; ++k)
+        if (k * G < L) {
+            const int idx = l + k * G;
+            uint32_t c = 0;
+            if (idx < L) {
+                float t = __builtin_fmaf(v[k] - lo, inv_scale, 0.5f);
+                asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));  // floor; NaN and negatives -> 0
+                c = c < 15u ? c : 15u;
+            }
+            uint32_t other = (uint32_t)__shfl_xor((int)c, 1, kWave);  // all lanes take part
+            if (live && (l & 1) == 0 && idx < L) codes[cbase + (idx >> 1)] = (uint8_t)(c | (other << 4));
+        }
+}
+
+template <bool BF16, int G>
+__global__ __launch_bounds__(kWave) void softmax_bwd_kernel(const void* dy,
+                                                            const uint8_t* __restrict__ codes,
+                                                            const float* __restrict__ qparams,
+                                                            void* dx, int64_t rows, int L)
+{
+    constexpr int RPW = kWave / G;
+    const int l = threadIdx.x % G;
+    const int64_t row = (int64_t)blockIdx.x * RPW + threadIdx.x / G;
+    const bool live = row < rows;
+    const int64_t base = row * L;
+    const int64_t cbase = row * ((L + 1) / 2);
+    const float lo = live ? qparams[2 * row] : 0.0f;
+    const float scale = live ? qparams[2 * row + 1] : 0.0f;
+
+    float yh[kSoftmaxSlots], g[kSoftmaxSlots];
+    float dot = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots; ++k) {
+        yh[k] = 0.0f;
+        g[k] = 0.0f;
+        if (k * G < L) {
+            const int idx = l + k * G;
+            if (live && idx < L) {
+                uint32_t q = (codes[cbase + (idx >> 1)] >> (4 * (idx & 1))) & 15u;
+                yh[k] = __builtin_fmaf((float)q, scale, lo);
+                g[k] = load_elem<BF16>(dy, base + idx);
+            }
+            dot = __builtin_fmaf(yh[k], g[k], dot);
+        }
+    }
+    dot = group_sum<G>(dot);
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots; ++k)
+        if (k * G < L) {
+            const int idx = l + k * G;
+            if (live && idx < L) store_elem<BF16>(dx, base + idx, yh[k] * (g[k] - dot));
+        }
+}
+
 }  // namespace s2a

@@ -23,9 +23,11 @@ ERR_NOT_INIT = -5
 ERR_LAUNCH = -6
 ERR_ALIGN = -7
 QSTATE_FLOATS = 544
+SOFTMAX_MAX_L = 1024
 
 EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd",
-           "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_relu_fwd", "s2a_relu_bwd", "s2a_strerror")
+           "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_relu_fwd", "s2a_relu_bwd",
+           "s2a_softmax_fwd", "s2a_softmax_bwd", "s2a_strerror")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libs2a.so")
 _lib = None
@@ -63,6 +65,10 @@ def lib() -> ctypes.CDLL:
         l.s2a_relu_fwd.argtypes = [vp, vp, vp, i64, i, vp]
         l.s2a_relu_bwd.restype = i
         l.s2a_relu_bwd.argtypes = [vp, vp, vp, i64, i, vp]
+        l.s2a_softmax_fwd.restype = i
+        l.s2a_softmax_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i, vp]
+        l.s2a_softmax_bwd.restype = i
+        l.s2a_softmax_bwd.argtypes = [vp, vp, vp, vp, i64, i64, i, vp]
         l.s2a_strerror.restype = ctypes.c_char_p
         l.s2a_strerror.argtypes = [i]
         _lib = l
@@ -132,4 +138,20 @@ def relu_bwd(dy: int, mask: int, dx: int, n: int, dtype: int, stream: int = 0, c
     rc = lib().s2a_relu_bwd(dy, mask, dx, int(n), int(dtype), stream)
     if check and rc != OK:
         raise S2AError(rc, "s2a_relu_bwd")
+    return rc
+
+
+def softmax_fwd(x: int, y: int, codes: int, qparams: int, rows: int, L: int, dtype: int, stream: int = 0,
+                check: bool = True) -> int:
+    rc = lib().s2a_softmax_fwd(x, y, codes, qparams, int(rows), int(L), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_softmax_fwd")
+    return rc
+
+
+def softmax_bwd(dy: int, codes: int, qparams: int, dx: int, rows: int, L: int, dtype: int, stream: int = 0,
+                check: bool = True) -> int:
+    rc = lib().s2a_softmax_bwd(dy, codes, qparams, dx, int(rows), int(L), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_softmax_bwd")
     return rc

@@ -33,6 +33,7 @@ def test_library_exports_every_declared_symbol():
 def test_error_paths_need_no_gpu():
     lib = ctypes.CDLL(s2a.LIB_PATH)  # same handle; state is process-global
     fake = ctypes.c_void_p(0x1000)   # never dereferenced: every call below fails validation first
+    odd_q = ctypes.c_void_p(0x1002)
     if lib.s2a_qtable_get(None, None, None) == s2a.ERR_NOT_INIT:
         assert s2a.act_fwd(fake, fake, fake, 8, s2a.F32, check=False) == s2a.ERR_NOT_INIT
         assert s2a.act_bwd(fake, fake, fake, 8, s2a.F32, check=False) == s2a.ERR_NOT_INIT
@@ -50,6 +51,12 @@ def test_error_paths_need_no_gpu():
         assert fn(None, None, None, 0, s2a.F32, check=False) == s2a.OK  # n == 0: nothing to do
     with pytest.raises(s2a.S2AError):
         s2a.act_fwd(None, fake, fake, 8, s2a.BF16)
+    # softmax entry points: checked before any device work, no table needed
+    assert s2a.softmax_fwd(fake, fake, fake, fake, 4, 0, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.softmax_fwd(fake, fake, fake, fake, 4, s2a.SOFTMAX_MAX_L + 1, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.softmax_bwd(fake, fake, fake, None, 4, 8, s2a.BF16, check=False) == s2a.ERR_NULL
+    assert s2a.softmax_bwd(fake, fake, odd_q, fake, 4, 8, s2a.BF16, check=False) == s2a.ERR_ALIGN
+    assert s2a.softmax_fwd(None, None, None, None, 0, 197, s2a.BF16, check=False) == s2a.OK
     # ReLU entry points need no table
     for fn in (s2a.relu_fwd, s2a.relu_bwd):
         assert fn(fake, fake, fake, 8, 3, check=False) == s2a.ERR_DTYPE

@@ -1,0 +1,165 @@
+"""GPU parity of the softmax-with-4-bit-y kernels (s2a_softmax_fwd / _bwd)
+against the oracle.
+
+Tolerances: y as for the activation path (1e-6 relative in fp32, 1 bf16 ulp);
+(min, scale) per row 1e-6 relative (1e-5 for bf16 storage, whose exponentials
+carry no compensated argument); codes bit-exact except where the real-valued
+level index t = (y - min)/scale lies within BAND_T of k + 1/2 (counted, and a
+differing code must be off by one).  dx is a difference of two terms, so its
+error is measured against their magnitudes: |err| <= 1e-5 * yh_i * (|dy_i| +
+sum_j yh_j |dy_j|)  (+ 2 bf16 ulps of the result for bf16 storage).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_08154_amd import s2a
+from paper_2503_08154_amd import workloads as wl
+
+import gpu_util as gu
+import parity
+
+pytestmark = pytest.mark.gpu
+DTYPES = [wl.F32, wl.BF16]
+BAND_T = {wl.F32: 5e-5, wl.BF16: 2e-4}
+QP_RTOL = {wl.F32: 1e-6, wl.BF16: 1e-5}
+
+
+def _logits(rows, L, dtype, seed, scale=2.0, masked=False):
+    g = np.random.Generator(np.random.Philox(seed))
+    a = g.standard_normal(rows * L) * scale
+    if masked and L > 2:
+        m = g.random(rows * L) < 0.15
+        m.reshape(rows, L)[:, 0] = False          # keep at least one finite entry per row
+        a[m] = -np.inf
+    return wl.to_storage(a, dtype)
+
+
+def _dx_scale(yh, dy, rows, L):
+    yh, dy = np.abs(yh.reshape(rows, L)), np.abs(dy.reshape(rows, L))
+    return (yh * (dy + (yh * dy).sum(axis=1, keepdims=True))).reshape(-1)
+
+
+def _check_dx(got_storage, ref, dtype, scale, factor=1.0, skip_rows=None, rows=0, L=0):
+    got = wl.storage_to_f64(got_storage, dtype)
+    tol = 1e-5 * factor * scale + 1e-300
+    if dtype == wl.BF16:
+        tol = tol + 2.0 * parity.bf16_ulp(ref)
+    bad = np.abs(got - ref) > tol
+    if skip_rows is not None:
+        bad.reshape(rows, L)[skip_rows] = False
+    assert not bad.any(), f"{int(bad.sum())} dx out of tolerance, first at {int(np.argmax(bad))}: " \
+                          f"{got[np.argmax(bad)]!r} vs {ref[np.argmax(bad)]!r}"
+
+
+def _run_and_check(x, dy, dtype, rows, L, offset=0):
+    n = rows * L
+    es = gu.esize(dtype)
+    rb = (L + 1) // 2
+    st = torch.cuda.current_stream().cuda_stream
+    y_ref, code_ref, packed_ref, qmin, qscale, near = oracle.softmax_fwd(x, dtype, rows, L, band_t=BAND_T[dtype])
+    bx = gu.Buf(n * es, offset * es).upload(x)
+    by = gu.Buf(n * es, offset * es, fill=0xFF)
+    bc = gu.Buf(rows * rb, offset, fill=0xFF)
+    bq = gu.Buf(8 * rows, fill=0xFF)
+    s2a.softmax_fwd(bx.ptr, by.ptr, bc.ptr, bq.ptr, rows, L, dtype, st)
+    torch.cuda.synchronize()
+    assert bx.canaries_intact() and by.canaries_intact() and bc.canaries_intact() and bq.canaries_intact()
+    y = by.download(gu.storage_np(dtype))
+    packed = bc.download(np.uint8)
+    qp = bq.download(np.float32).reshape(rows, 2)
+    finite_rows = np.isfinite(y_ref.reshape(rows, L)).all(axis=1)
+    parity.check_values(y, y_ref, dtype, "y", finite_in=np.repeat(finite_rows, L))
+    np.testing.assert_allclose(qp[finite_rows, 0], qmin[finite_rows], rtol=QP_RTOL[dtype], atol=1e-37)
+    np.testing.assert_allclose(qp[finite_rows, 1], qscale[finite_rows], rtol=QP_RTOL[dtype] * 4, atol=1e-37)
+    # codes, row by row (each row starts on a byte)
+    got = np.stack([parity.unpack(packed[r * rb:(r + 1) * rb], L) for r in range(rows)]).reshape(-1) if rows else np.empty(0, np.uint8)
+    diff = (got != code_ref) & np.repeat(finite_rows, L)
+    assert not (diff & (near == 0)).any(), "a code differs outside the band"
+    if diff.any():
+        assert (np.abs(got[diff].astype(int) - code_ref[diff].astype(int)) == 1).all()
+    if L % 2 and rows:
+        assert (packed.reshape(rows, rb)[:, -1] >> 4 == 0).all(), "pad nibble not zero"
+    # backward alone: the oracle's codes and its (min, scale) rounded to fp32 go in
+    qp32 = np.stack([qmin, qscale], axis=1).astype(np.float32)
+    dx_ref = oracle.softmax_bwd(dy, dtype, packed_ref, qp32[:, 0].astype(np.float64), qp32[:, 1].astype(np.float64), rows, L)
+    yh = code_ref * np.repeat(qp32[:, 1].astype(np.float64), L) + np.repeat(qp32[:, 0].astype(np.float64), L)
+    scale = _dx_scale(yh, wl.storage_to_f64(dy, dtype), rows, L)
+    bdy = gu.Buf(n * es, offset * es).upload(dy)
+    bdx = gu.Buf(n * es, offset * es, fill=0xFF)
+    bc2 = gu.Buf(rows * rb, offset).upload(packed_ref)
+    bq2 = gu.Buf(8 * rows).upload(qp32.reshape(-1))
+    s2a.softmax_bwd(bdy.ptr, bc2.ptr, bq2.ptr, bdx.ptr, rows, L, dtype, st)
+    torch.cuda.synchronize()
+    assert bdx.canaries_intact() and bdy.canaries_intact()
+    bad_rows = ~finite_rows
+    _check_dx(bdx.download(gu.storage_np(dtype)), dx_ref, dtype, scale, skip_rows=bad_rows, rows=rows, L=L)
+    # end to end: the GPU's own codes and parameters; rows with a legitimately differing code are skipped
+    s2a.softmax_bwd(bdy.ptr, bc.ptr, bq.ptr, bdx.ptr, rows, L, dtype, st)
+    torch.cuda.synchronize()
+    dx_ref2 = oracle.softmax_bwd(dy, dtype, packed_ref, qmin, qscale, rows, L)
+    skip = bad_rows | diff.reshape(rows, L).any(axis=1) if rows else None
+    _check_dx(bdx.download(gu.storage_np(dtype)), dx_ref2, dtype, scale, factor=10.0 if dtype == wl.BF16 else 2.0,
+              skip_rows=skip, rows=rows, L=L)
+    return int(near.sum()), int(diff.sum())
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("L", [1, 2, 3, 7, 8, 9, 16, 17, 49, 64, 65, 127, 128, 129, 196, 197, 256, 257,
+                               511, 512, 513, 1023, 1024])
+def test_row_lengths(dtype, L):
+    for rows in (1, 5, 67):
+        x = _logits(rows, L, dtype, seed=L * 10 + rows)
+        dy = wl.draw_dy(rows * L, 1.0, dtype, seed=L * 10 + rows + 1)
+        _run_and_check(x, dy, dtype, rows, L)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("L", [49, 197, 257])
+def test_masked_and_peaked_rows(dtype, L):
+    rows = 333
+    x = _logits(rows, L, dtype, seed=5 + L, scale=6.0, masked=True)
+    dy = wl.draw_dy(rows * L, 1e-2, dtype, seed=6 + L)
+    _run_and_check(x, dy, dtype, rows, L)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_constant_and_two_valued_rows(dtype):
+    L, rows = 197, 4
+    a = np.zeros((rows, L))
+    a[1] = 0.75                      # constant rows: scale 0, codes 0
+    a[2, ::2] = 1.0                  # two values: codes 0 and 15 only
+    a[3, 5] = 30.0                   # one dominant entry
+    x = wl.to_storage(a.reshape(-1), dtype)
+    dy = wl.draw_dy(rows * L, 1.0, dtype, seed=3)
+    _run_and_check(x, dy, dtype, rows, L)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_unaligned_buffers(dtype):
+    rows, L = 50, 197
+    x = _logits(rows, L, dtype, seed=77)
+    dy = wl.draw_dy(rows * L, 1.0, dtype, seed=78)
+    _run_and_check(x, dy, dtype, rows, L, offset=1)
+
+
+def test_argument_errors():
+    fake = 0x1000
+    assert s2a.softmax_fwd(fake, fake, fake, fake, 4, 0, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.softmax_fwd(fake, fake, fake, fake, 4, 1025, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.softmax_fwd(fake, fake, fake, fake, -1, 8, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.softmax_fwd(fake, fake, fake, fake, 4, 8, 9, check=False) == s2a.ERR_DTYPE
+    assert s2a.softmax_fwd(fake, None, fake, fake, 4, 8, s2a.F32, check=False) == s2a.ERR_NULL
+    assert s2a.softmax_bwd(fake, fake, 0x1002, fake, 4, 8, s2a.F32, check=False) == s2a.ERR_ALIGN
+    assert s2a.softmax_fwd(None, None, None, None, 0, 8, s2a.F32, check=False) == s2a.OK
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_vit_b16_attention_full_size(dtype):
+    """ViT-B/16 attention probabilities of one layer: [64, 12, 197, 197] -> 151,296 rows of 197."""
+    rows, L = 64 * 12 * 197, 197
+    x = _logits(rows, L, dtype, seed=2024)
+    dy = wl.draw_dy(rows * L, 1e-2, dtype, seed=2025)
+    near, differing = _run_and_check(x, dy, dtype, rows, L)
+    print(f"\n[softmax vit_b16 attention dtype={dtype}] n={rows * L} in-band={near} differing={differing}")
