@@ -140,6 +140,53 @@ def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds
     return res
 
 
+def time_softmax(torch, rows: int, L: int, dtype: int, sets: int, steps: int, warmup: int):
+    """Softmax with 4-bit y on `sets` distinct buffer sets of [rows, L] logits (N(0, 2^2))."""
+    n = rows * L
+    rb = (L + 1) // 2
+    g = np.random.Generator(np.random.Philox(wl.layer_seed(wl.WORKLOADS["vit_b16"], 0, 0) + 7))
+    x = wl.to_storage(g.standard_normal(n) * 2.0, dtype)
+    dy = wl.draw_dy(n, 1e-2, dtype, 4711)
+    bufs = []
+    for _ in range(sets):
+        tx = torch.from_numpy(x.view(np.uint8)).cuda()
+        tdy = torch.from_numpy(dy.view(np.uint8)).cuda()
+        bufs.append((tx, torch.empty_like(tx), torch.empty(rows * rb, dtype=torch.uint8, device="cuda"),
+                     torch.empty(2 * rows, dtype=torch.float32, device="cuda"), tdy, torch.empty_like(tdy)))
+    ptrs = [tuple(t.data_ptr() for t in b) for b in bufs]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        for p in ptrs:
+            s2a.softmax_fwd(p[0], p[1], p[2], p[3], rows, L, dtype, stream)
+        if ev:
+            ev[1].record()
+        for p in reversed(ptrs):
+            s2a.softmax_bwd(p[4], p[2], p[3], p[5], rows, L, dtype, stream)
+        if ev:
+            ev[2].record()
+
+    for _ in range(warmup):
+        step()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for k in range(steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    fwd_us = sum(e[0].elapsed_time(e[1]) for e in events) * 1e3 / (steps * sets)
+    bwd_us = sum(e[1].elapsed_time(e[2]) for e in events) * 1e3 / (steps * sets)
+    nbytes = 2 * esize(dtype) * n + rows * rb + 8 * rows
+    return {
+        "shape": f"[{rows}, {L}] " + ("bf16" if dtype == wl.BF16 else "f32"),
+        "fwd_us": round(fwd_us, 2), "bwd_us": round(bwd_us, 2),
+        "fwd_gbs": round(nbytes / fwd_us / 1e3, 1), "fwd_frac": round(nbytes / fwd_us / 1e3 / HBM_PEAK_GBS, 4),
+        "bwd_gbs": round(nbytes / bwd_us / 1e3, 1), "bwd_frac": round(nbytes / bwd_us / 1e3 / HBM_PEAK_GBS, 4),
+        "algorithmic_bytes_per_launch": nbytes, "buffer_sets": sets,
+    }
+
+
 def roofline_of(res, w: wl.Workload):
     """Roofline entry of the slower of the two kernels."""
     which = "fwd" if res["fwd_us_per_launch"] >= res["bwd_us_per_launch"] else "bwd"
@@ -295,6 +342,11 @@ def main():
             "bwd_gbs": round(relu_bytes / r["bwd_us_per_launch"] / 1e3, 1),
             "bwd_frac": round(relu_bytes / r["bwd_us_per_launch"] / 1e3 / HBM_PEAK_GBS, 4),
             "algorithmic_bytes_per_launch": relu_bytes,
+        }
+        # next row: softmax with 4-bit y on the ViT-B/16 attention shape [64*12*197, 197]
+        out["softmax_4bit"] = {
+            "vit_b16_attention_bf16": time_softmax(torch, 64 * 12 * 197, 197, wl.BF16, 12, max(5, args.steps // 2), 5),
+            "vit_b16_attention_f32": time_softmax(torch, 64 * 12 * 197, 197, wl.F32, 8, max(5, args.steps // 2), 5),
         }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -185,24 +185,53 @@ int softmax_group(int64_t L)
     return 0;
 }
 
+// LDS bytes of one softmax block: the data span (+ up to 15 bytes of lead-in and
+// padding to a vector), then the codes span.
+template <bool BF16, int G>
+void softmax_lds(int L, int* data_bytes, int* codes_bytes, int* total_bytes)
+{
+    const int rpb = s2a::kSoftmaxBlock / G, es = BF16 ? 2 : 4;
+    *data_bytes = ((rpb * L * es + 15 + 15) / 16) * 16;
+    *codes_bytes = ((rpb * ((L + 1) / 2) + 15 + 15) / 16) * 16;
+    *total_bytes = *data_bytes + *codes_bytes + 16;  // + the spare slot dead lanes write to
+}
+
 template <bool BF16, int G>
 int launch_softmax_fwd_g(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
                          hipStream_t st)
 {
-    int64_t blocks = (rows + (s2a::kWave / G) - 1) / (s2a::kWave / G);
+    const int rpb = s2a::kSoftmaxBlock / G;
+    int64_t blocks = (rows + rpb - 1) / rpb;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    int data_bytes, codes_bytes, total;
+    softmax_lds<BF16, G>(L, &data_bytes, &codes_bytes, &total);
+    const bool staged = aligned(x, 16) && aligned(y, 16) && aligned(codes, 16);
     return checked_launch([&] {
-        s2a::softmax_fwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(x, y, codes, qp, rows, L);
+        if (staged)
+            s2a::softmax_fwd_staged<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
+                x, y, codes, qp, rows, L, data_bytes, codes_bytes);
+        else
+            s2a::softmax_fwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
+                x, y, codes, qp, rows, L);
     });
 }
 template <bool BF16, int G>
 int launch_softmax_bwd_g(const void* dy, const uint8_t* codes, const float* qp, void* dx,
                          int64_t rows, int L, hipStream_t st)
 {
-    int64_t blocks = (rows + (s2a::kWave / G) - 1) / (s2a::kWave / G);
+    const int rpb = s2a::kSoftmaxBlock / G;
+    int64_t blocks = (rows + rpb - 1) / rpb;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    int data_bytes, codes_bytes, total;
+    softmax_lds<BF16, G>(L, &data_bytes, &codes_bytes, &total);
+    const bool staged = aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 16);
     return checked_launch([&] {
-        s2a::softmax_bwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(dy, codes, qp, dx, rows, L);
+        if (staged)
+            s2a::softmax_bwd_staged<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
+                dy, codes, qp, dx, rows, L, data_bytes, codes_bytes);
+        else
+            s2a::softmax_bwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
+                dy, codes, qp, dx, rows, L);
     });
 }
 template <bool BF16>

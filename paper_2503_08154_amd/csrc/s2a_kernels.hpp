@@ -656,48 +656,87 @@ __global__ __launch_bounds__(kBlock) void relu_bwd_kernel_unaligned(const void* 
 //
 // A row is handled by a group of G lanes (G = 8, 16, 32 or 64, the smallest with
 // ceil(L/G) <= 16), so a wave holds 64/G rows and all row reductions are
-// cross-lane shuffles inside the group: no LDS, no barrier.  Lane l of the
+// cross-lane shuffles inside the group.  Lane l of the
 // group owns elements l, l+G, l+2G, ...; since G is even, elements 2j and 2j+1
 // sit in neighbouring lanes at the same step, and the even lane packs both
 // codes into the byte it stores.
 constexpr int kSoftmaxSlots = 16;    // elements per lane at most
 constexpr int kSoftmaxMaxL = 64 * kSoftmaxSlots;
 
-template <int G>
-__device__ __forceinline__ float group_max(float v)
+// Cross-lane moves inside a row of 16 lanes as DPP operand modifiers (no LDS
+// traffic, one VALU op each): swap with the neighbour (xor 1), with the other
+// pair of the quad (xor 2), mirror the 8 / the 16 lanes of a half row / row.
+// After the quads agree, the two mirrors pair every lane with one from the
+// other half, so for all-reduce purposes they act as xor 4 and xor 8.  Every
+// lane of the wave must be active.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v)
 {
-#pragma unroll
-    for (int off = G / 2; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, dpp_move<CTRL>(__builtin_bit_cast(int, v)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v)
+{
+    uint64_t u = __builtin_bit_cast(uint64_t, v);
+    uint32_t lo = (uint32_t)dpp_move<CTRL>((int)(uint32_t)u), hi = (uint32_t)dpp_move<CTRL>((int)(uint32_t)(u >> 32));
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+// v_max_f32 / v_min_f32 as single instructions.  (The portable fmaxf / fminf
+// first re-quiet every operand the compiler cannot prove canonical -- here all
+// of them, since they come from bit patterns -- which doubles the op count.)
+// NaN operands lose against numbers, as with fmaxf / fminf.
+__device__ __forceinline__ float vmax(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmin(float a, float b)
+{
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// All-reduce over the G lanes of a row group; F(a, b) is the (commutative) combiner.
+template <int G, typename T, typename F>
+__device__ __forceinline__ T group_reduce(T v, F f)
+{
+    v = f(v, dpp_move<kDppXor1>(v));
+    v = f(v, dpp_move<kDppXor2>(v));
+    v = f(v, dpp_move<kDppHalfMirror>(v));
+    if (G >= 16) v = f(v, dpp_move<kDppMirror>(v));
+    if (G >= 32) v = f(v, __shfl_xor(v, 16, kWave));
+    if (G >= 64) v = f(v, __shfl_xor(v, 32, kWave));
     return v;
 }
 template <int G>
-__device__ __forceinline__ float group_min(float v)
-{
-#pragma unroll
-    for (int off = G / 2; off > 0; off >>= 1) v = fminf(v, __shfl_xor(v, off, kWave));
-    return v;
-}
+__device__ __forceinline__ float group_max(float v) { return group_reduce<G>(v, [](float a, float b) { return vmax(a, b); }); }
+template <int G>
+__device__ __forceinline__ float group_min(float v) { return group_reduce<G>(v, [](float a, float b) { return vmin(a, b); }); }
 template <int G, typename T>
-__device__ __forceinline__ T group_sum(T v)
-{
-#pragma unroll
-    for (int off = G / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
-}
+__device__ __forceinline__ T group_sum(T v) { return group_reduce<G>(v, [](T a, T b) { return a + b; }); }
 
 // exp(x - m) for x <= m.  The bf16 storage path takes the plain route.  The
 // fp32 storage path keeps 1e-6 relative accuracy down to the smallest results:
 // the difference x - m is formed exactly as s + err (two-sum), and the exponent
 // (s + err) * log2(e) as an exact hi + lo pair; otherwise the rounding of the
 // difference alone costs 2e-6 relative at x - m = -36.  Differences below -200
-// (e^-200 is 0 in fp32; this includes masked logits of -inf) return 0.
+// (e^-200 is 0 in fp32; this includes masked logits of -inf) return 0 there.
 template <bool BF16>
 __device__ __forceinline__ float exp_diff(float x, float m)
 {
     constexpr double kL2e = 1.4426950408889634074;
     constexpr float hi = (float)kL2e, lo = (float)(kL2e - (double)hi);
     float s = x - m;
-    if (BF16) return __builtin_amdgcn_exp2f(fmaxf(s, -200.0f) * hi);
+    if (BF16) return __builtin_amdgcn_exp2f(s * hi);  // -inf -> 0 by itself
     float bb = s - x;
     float err = (x - (s - bb)) + (-m - bb);
     const bool ok = s > -200.0f;  // false for -inf and NaN as well
@@ -710,95 +749,346 @@ __device__ __forceinline__ float exp_diff(float x, float m)
     return __builtin_amdgcn_exp2f(t) * __builtin_fmaf(tl, kLn2, 1.0f);
 }
 
-template <bool BF16, int G>
-__global__ __launch_bounds__(kWave) void softmax_fwd_kernel(const void* x, void* y,
-                                                            uint8_t* __restrict__ codes,
-                                                            float* __restrict__ qparams,
-                                                            int64_t rows, int L)
+// Staging.  A block of kSoftmaxBlock lanes owns kSoftmaxBlock/G consecutive
+// rows, i.e. one contiguous span of x (and of y, codes).  Row starts are only
+// element-aligned (L = 197 bf16 -> 394-byte rows), so per-row access would be a
+// stream of 2-byte loads; instead the span is moved between HBM and LDS with
+// 16-byte vectors (its ragged first and last vector element by element), and the
+// row-shaped access pattern hits LDS.  The LDS copy keeps the span's offset
+// within its first 16-byte vector, so global vectors map onto aligned LDS
+// vectors.  Measured at the ViT-B/16 attention shape: 24 % -> see the design
+// notes for the staged figure.
+constexpr int kSoftmaxBlock = 256;
+
+// Copy bytes [a, b) of `src` (global, `total` bytes long, 16-byte aligned) to
+// lds + (p - (a & ~15)).  Whole 16-byte vectors are moved, including the first
+// and last one, which also carry a few bytes of the neighbouring blocks' rows
+// (never used); only a vector that would cross the end of the tensor is read
+// element by element, one element per lane (UNIT = bytes per element).  Up to
+// four loads per lane are in flight before the first LDS write waits for data.
+template <int UNIT>
+__device__ __forceinline__ void copy_unit(unsigned char* dst, const unsigned char* src)
 {
-    constexpr int RPW = kWave / G;  // rows per wave
-    const int l = threadIdx.x % G;
-    const int64_t row = (int64_t)blockIdx.x * RPW + threadIdx.x / G;
+    if (UNIT == 4) *(uint32_t*)dst = *(const uint32_t*)src;
+    else if (UNIT == 2) *(uint16_t*)dst = *(const uint16_t*)src;
+    else *dst = *src;
+}
+template <int UNIT>
+__device__ __forceinline__ void stage_in(const void* src, unsigned char* lds, int64_t a, int64_t b,
+                                         int64_t total)
+{
+    const int64_t a_dn = a & ~(int64_t)15;
+    const unsigned char* g0 = (const unsigned char*)src + a_dn;  // uniform over the block
+    const int head = (int)(a - a_dn), span = (int)(b - a_dn);
+    const int nv = (span + 15) >> 4;
+    const bool cut = a_dn + 16 * (int64_t)nv > total;            // the tensor ends inside the last vector
+    const int nfull = cut ? nv - 1 : nv;
+    const int tid = (int)threadIdx.x;
+    constexpr int U = 4;
+    for (int base = 0; base < nfull; base += U * kSoftmaxBlock) {
+        u32x4 t[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = base + u * kSoftmaxBlock + tid;
+            if (i < nfull) t[u] = stream_load128((const u32x4*)(g0 + 16 * i));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = base + u * kSoftmaxBlock + tid;
+            if (i < nfull) *(u32x4*)(lds + 16 * i) = t[u];
+        }
+    }
+    if (cut && tid < 16 / UNIT) {
+        const int p = 16 * (nv - 1) + tid * UNIT;
+        if (p >= head && p < span) copy_unit<UNIT>(lds + p, g0 + p);
+    }
+}
+// The reverse copy.  Vectors that lie wholly inside [a, b) are stored as such;
+// the ragged first and last vector belong partly to other blocks and are
+// written element by element, one element per lane.
+template <int UNIT>
+__device__ __forceinline__ void stage_out(void* dst, const unsigned char* lds, int64_t a, int64_t b)
+{
+    const int64_t a_dn = a & ~(int64_t)15;
+    unsigned char* g0 = (unsigned char*)dst + a_dn;
+    const int head = (int)(a - a_dn), span = (int)(b - a_dn);
+    const int first_full = head ? 1 : 0, last_full = span >> 4;  // vectors [first_full, last_full) are whole
+    const int tid = (int)threadIdx.x;
+    for (int i = first_full + tid; i < last_full; i += kSoftmaxBlock)
+        stream_store128((u32x4*)(g0 + 16 * i), *(const u32x4*)(lds + 16 * i));
+    constexpr int PER = 16 / UNIT;
+    if (tid < 2 * PER) {
+        const bool tail = tid >= PER;
+        const int p = tail ? 16 * last_full + (tid - PER) * UNIT : tid * UNIT;
+        const bool want = tail ? !(first_full == 1 && last_full == 0) : first_full == 1;
+        if (want && p >= head && p < span && (tail || p < 16)) copy_unit<UNIT>(g0 + p, lds + p);
+    }
+}
+
+// ---- staged kernels: x, y (dy, dx) and codes 16-byte aligned (the launcher checks) ----
+//
+// Straight-line per lane: only the last slot of a row (k = (L-1)/G) can hold
+// lanes past the row end, so every earlier slot runs without predicates; rows
+// past the end of the tensor (last block only) shadow the block's last real
+// row and send their LDS writes to a spare slot.  `data_bytes` is the size of
+// the LDS data area; the codes area follows it, and 16 spare bytes follow that.
+
+template <bool BF16>
+__device__ __forceinline__ float lds_in(const unsigned char* p)
+{
+    return BF16 ? as_f32((uint32_t)(*(const uint16_t*)p) << 16) : *(const float*)p;
+}
+template <bool BF16>
+__device__ __forceinline__ void lds_out(unsigned char* p, float v)
+{
+    if (BF16) *(uint16_t*)p = (uint16_t)pack_bf16(v, 0.0f); else *(float*)p = v;
+}
+
+template <bool BF16, int G>
+__global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* x, void* y,
+                                                                    uint8_t* codes,
+                                                                    float* __restrict__ qparams,
+                                                                    int64_t rows, int L,
+                                                                    int data_bytes, int codes_bytes)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int RPB = kSoftmaxBlock / G;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int l = threadIdx.x % G, lrow = threadIdx.x / G;
+    const int64_t row0 = (int64_t)blockIdx.x * RPB;
+    const int nrows = rows - row0 < RPB ? (int)(rows - row0) : RPB;
+    const bool live = lrow < nrows;
+    const int srow = live ? lrow : nrows - 1;  // dead lanes shadow the last real row
+    const int rb = (L + 1) / 2;
+    const int64_t xa = row0 * L * ES, xb = (row0 + nrows) * L * ES;
+    const int64_t ca = row0 * rb, cb = (row0 + nrows) * rb;
+    unsigned char* spare = lds + data_bytes + codes_bytes;
+    // this lane's element of slot 0, and the byte its pair shares, inside LDS
+    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + l) * ES;
+    unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
+    const int klast = (L - 1) / G;            // the only slot that can be partly empty
+    const int ilast = l + klast * G;          // this lane's element index in that slot
+    const bool has_last = ilast < L;
+    const float ninf = -__builtin_inff(), pinf = __builtin_inff();
+    const int own_shift = (l & 1) * 4, other_shift = 4 - own_shift;
+
+    stage_in<ES>(x, lds, xa, xb, rows * L * ES);
+    __syncthreads();
+
+    // pass 1: load, row maximum and minimum
+    float v[kSoftmaxSlots];
+    float m = ninf, xmin = pinf;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+        if (k < klast) {
+            v[k] = lds_in<BF16>(lx + k * G * ES);
+            m = vmax(m, v[k]);
+            xmin = vmin(xmin, v[k]);
+        }
+    float vl = lds_in<BF16>(lx + ((has_last ? ilast : L - 1) - l) * ES);
+    m = vmax(m, has_last ? vl : ninf);
+    xmin = vmin(xmin, has_last ? vl : pinf);
+    m = group_max<G>(m);
+    xmin = group_min<G>(xmin);
+
+    // pass 2: exponentials and their sum
+    typedef typename std::conditional<BF16, float, double>::type acc_t;
+    acc_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+        if (k < klast) {
+            v[k] = exp_diff<BF16>(v[k], m);
+            sum += (acc_t)v[k];
+        }
+    vl = has_last ? exp_diff<BF16>(vl, m) : 0.0f;
+    sum += (acc_t)vl;
+    sum = group_sum<G>(sum);
+    const float inv = (float)((acc_t)1 / sum);
+    // y is monotone in x, so its extremes are the images of the row's extremes
+    const float hi = exp_diff<BF16>(m, m) * inv;
+    const float lo = exp_diff<BF16>(xmin, m) * inv;
+    const float scale = (hi - lo) / 15.0f;
+    const float inv_scale = scale > 0.0f ? 15.0f / (hi - lo) : 0.0f;
+    if (live && l == 0) {
+        qparams[2 * (row0 + lrow)] = lo;
+        qparams[2 * (row0 + lrow) + 1] = scale;
+    }
+
+    // pass 3: y and the codes into LDS.  Both lanes of a pair form the same byte
+    // and write it to the same place.
+    auto quantize = [&](float yk) -> uint32_t {
+        float t = __builtin_fmaf(yk - lo, inv_scale, 0.5f);
+        uint32_t c;
+        asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));  // floor; NaN and negatives -> 0
+        return c < 15u ? c : 15u;
+    };
+    unsigned char* wy = live ? lx : spare;   // dead rows write to the spare slot
+    unsigned char* wc = live ? lc : spare;
+    const int ystep = live ? G * ES : 0, cstep = live ? G / 2 : 0;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+        if (k < klast) {
+            const float yk = v[k] * inv;
+            const uint32_t c = quantize(yk);
+            const uint32_t other = (uint32_t)dpp_move<kDppXor1>((int)c);
+            lds_out<BF16>(wy + k * ystep, yk);
+            wc[k * cstep] = (uint8_t)((c << own_shift) | (other << other_shift));
+        }
+    {
+        const float yk = vl * inv;
+        const uint32_t c = has_last ? quantize(yk) : 0u;  // 0 = pad nibble
+        const uint32_t other = (uint32_t)dpp_move<kDppXor1>((int)c);
+        // a lane past the row end still writes the shared byte if its partner is the row's last element
+        const bool byte_in_row = (ilast & ~1) < L;
+        lds_out<BF16>(live && has_last ? lx + klast * G * ES : spare, yk);
+        *(live && byte_in_row ? lc + klast * (G / 2) : spare) = (uint8_t)((c << own_shift) | (other << other_shift));
+    }
+    __syncthreads();
+    stage_out<ES>(y, lds, xa, xb);
+    stage_out<1>(codes, lds + data_bytes, ca, cb);
+}
+
+template <bool BF16, int G>
+__global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* dy,
+                                                                    const uint8_t* codes,
+                                                                    const float* __restrict__ qparams,
+                                                                    void* dx, int64_t rows, int L,
+                                                                    int data_bytes, int codes_bytes)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int RPB = kSoftmaxBlock / G;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int l = threadIdx.x % G, lrow = threadIdx.x / G;
+    const int64_t row0 = (int64_t)blockIdx.x * RPB;
+    const int nrows = rows - row0 < RPB ? (int)(rows - row0) : RPB;
+    const bool live = lrow < nrows;
+    const int srow = live ? lrow : nrows - 1;
+    const int rb = (L + 1) / 2;
+    const int64_t xa = row0 * L * ES, xb = (row0 + nrows) * L * ES;
+    const int64_t ca = row0 * rb, cb = (row0 + nrows) * rb;
+    unsigned char* spare = lds + data_bytes + codes_bytes;
+    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + l) * ES;
+    const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
+    const int klast = (L - 1) / G;
+    const int ilast = l + klast * G;
+    const bool has_last = ilast < L;
+    const int nib_shift = (l & 1) * 4;
+
+    stage_in<ES>(dy, lds, xa, xb, rows * L * ES);
+    stage_in<1>(codes, lds + data_bytes, ca, cb, rows * rb);
+    const float lo = qparams[2 * (row0 + srow)];
+    const float scale = qparams[2 * (row0 + srow) + 1];
+    __syncthreads();
+
+    auto dequant = [&](uint32_t byte) { return __builtin_fmaf((float)((byte >> nib_shift) & 15u), scale, lo); };
+    float yh[kSoftmaxSlots], g[kSoftmaxSlots];
+    float dot = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+        if (k < klast) {
+            yh[k] = dequant(lc[k * (G / 2)]);
+            g[k] = lds_in<BF16>(lx + k * G * ES);
+            dot = __builtin_fmaf(yh[k], g[k], dot);
+        }
+    const int sl = (has_last ? ilast : L - 1) - l;  // a safe element for lanes past the row end
+    float yl = dequant(lc[(has_last ? klast * (G / 2) : ((L - 1) >> 1) - (l >> 1))]);
+    float gl = lds_in<BF16>(lx + sl * ES);
+    yl = has_last ? yl : 0.0f;
+    gl = has_last ? gl : 0.0f;
+    dot = __builtin_fmaf(yl, gl, dot);
+    dot = group_sum<G>(dot);
+
+    unsigned char* wx = live ? lx : spare;
+    const int xstep = live ? G * ES : 0;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+        if (k < klast) lds_out<BF16>(wx + k * xstep, yh[k] * (g[k] - dot));
+    lds_out<BF16>(live && has_last ? lx + klast * G * ES : spare, yl * (gl - dot));
+    __syncthreads();
+    stage_out<ES>(dx, lds, xa, xb);
+}
+
+// ---- element-wise kernels for buffers that are not 16-byte aligned (same results, not tuned) ----
+
+template <bool BF16, int G>
+__global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_kernel(const void* x, void* y,
+                                                                    uint8_t* codes,
+                                                                    float* __restrict__ qparams,
+                                                                    int64_t rows, int L)
+{
+    constexpr int RPB = kSoftmaxBlock / G;
+    const int l = threadIdx.x % G, lrow = threadIdx.x / G;
+    const int64_t row = (int64_t)blockIdx.x * RPB + lrow;
     const bool live = row < rows;
-    const int64_t base = row * L;
-    const float ninf = -__builtin_inff();
+    const int rb = (L + 1) / 2;
+    const float ninf = -__builtin_inff(), pinf = __builtin_inff();
 
     float v[kSoftmaxSlots];
-    float m = ninf;
+    float m = ninf, xmin = pinf;
 #pragma unroll
     for (int k = 0; k < kSoftmaxSlots; ++k) {
         v[k] = ninf;
-        if (k * G < L) {  // uniform over the wave
+        if (k * G < L) {  // uniform over the block
             const int idx = l + k * G;
-            if (live && idx < L) v[k] = load_elem<BF16>(x, base + idx);
-            m = fmaxf(m, v[k]);
+            if (live && idx < L) {
+                v[k] = load_elem<BF16>(x, row * L + idx);
+                xmin = vmin(xmin, v[k]);
+            }
+            m = vmax(m, v[k]);
         }
     }
     m = group_max<G>(m);
-
-    // the fp32 storage path sums in double: 197 fp32 additions could otherwise eat the 1e-6 budget
+    xmin = group_min<G>(xmin);
     typedef typename std::conditional<BF16, float, double>::type acc_t;
     acc_t sum = 0;
 #pragma unroll
     for (int k = 0; k < kSoftmaxSlots; ++k)
         if (k * G < L) {
-            v[k] = exp_diff<BF16>(v[k], m);  // slots past the row end hold -inf -> 0
+            v[k] = exp_diff<BF16>(v[k], m);
             sum += (acc_t)v[k];
         }
     sum = group_sum<G>(sum);
     const float inv = (float)((acc_t)1 / sum);
-
-    float lo = __builtin_inff(), hi = ninf;
-#pragma unroll
-    for (int k = 0; k < kSoftmaxSlots; ++k)
-        if (k * G < L) {
-            const int idx = l + k * G;
-            v[k] *= inv;
-            if (idx < L) {
-                lo = fminf(lo, v[k]);
-                hi = fmaxf(hi, v[k]);
-                if (live) store_elem<BF16>(y, base + idx, v[k]);
-            }
-        }
-    lo = group_min<G>(lo);
-    hi = group_max<G>(hi);
+    const float hi = exp_diff<BF16>(m, m) * inv;
+    const float lo = exp_diff<BF16>(xmin, m) * inv;
     const float scale = (hi - lo) / 15.0f;
     const float inv_scale = scale > 0.0f ? 15.0f / (hi - lo) : 0.0f;
     if (live && l == 0) {
         qparams[2 * row] = lo;
         qparams[2 * row + 1] = scale;
     }
-    const int64_t cbase = row * ((L + 1) / 2);
 #pragma unroll
     for (int k = 0; k < kSoftmaxSlots; ++k)
         if (k * G < L) {
             const int idx = l + k * G;
+            const float yk = v[k] * inv;
             uint32_t c = 0;
             if (idx < L) {
-                float t = __builtin_fmaf(v[k] - lo, inv_scale, 0.5f);
-                asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));  // floor; NaN and negatives -> 0
+                float t = __builtin_fmaf(yk - lo, inv_scale, 0.5f);
+                asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));
                 c = c < 15u ? c : 15u;
             }
-            uint32_t other = (uint32_t)__shfl_xor((int)c, 1, kWave);  // all lanes take part
-            if (live && (l & 1) == 0 && idx < L) codes[cbase + (idx >> 1)] = (uint8_t)(c | (other << 4));
+            const uint32_t other = (uint32_t)dpp_move<kDppXor1>((int)c);  // all lanes take part
+            if (live && idx < L) {
+                store_elem<BF16>(y, row * L + idx, yk);
+                if ((l & 1) == 0) codes[row * rb + (idx >> 1)] = (uint8_t)(c | (other << 4));
+            }
         }
 }
 
 template <bool BF16, int G>
-__global__ __launch_bounds__(kWave) void softmax_bwd_kernel(const void* dy,
-                                                            const uint8_t* __restrict__ codes,
-                                                            const float* __restrict__ qparams,
-                                                            void* dx, int64_t rows, int L)
+__global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_kernel(const void* dy,
+                                                                    const uint8_t* codes,
+                                                                    const float* __restrict__ qparams,
+                                                                    void* dx, int64_t rows, int L)
 {
-    constexpr int RPW = kWave / G;
-    const int l = threadIdx.x % G;
-    const int64_t row = (int64_t)blockIdx.x * RPW + threadIdx.x / G;
+    constexpr int RPB = kSoftmaxBlock / G;
+    const int l = threadIdx.x % G, lrow = threadIdx.x / G;
+    const int64_t row = (int64_t)blockIdx.x * RPB + lrow;
     const bool live = row < rows;
-    const int64_t base = row * L;
-    const int64_t cbase = row * ((L + 1) / 2);
+    const int rb = (L + 1) / 2;
     const float lo = live ? qparams[2 * row] : 0.0f;
     const float scale = live ? qparams[2 * row + 1] : 0.0f;
-
     float yh[kSoftmaxSlots], g[kSoftmaxSlots];
     float dot = 0.0f;
 #pragma unroll
@@ -808,9 +1098,9 @@ __global__ __launch_bounds__(kWave) void softmax_bwd_kernel(const void* dy,
         if (k * G < L) {
             const int idx = l + k * G;
             if (live && idx < L) {
-                uint32_t q = (codes[cbase + (idx >> 1)] >> (4 * (idx & 1))) & 15u;
-                yh[k] = __builtin_fmaf((float)q, scale, lo);
-                g[k] = load_elem<BF16>(dy, base + idx);
+                const uint32_t byte = codes[row * rb + (idx >> 1)];
+                yh[k] = __builtin_fmaf((float)((byte >> (4 * (idx & 1))) & 15u), scale, lo);
+                g[k] = load_elem<BF16>(dy, row * L + idx);
             }
             dot = __builtin_fmaf(yh[k], g[k], dot);
         }
@@ -820,7 +1110,7 @@ __global__ __launch_bounds__(kWave) void softmax_bwd_kernel(const void* dy,
     for (int k = 0; k < kSoftmaxSlots; ++k)
         if (k * G < L) {
             const int idx = l + k * G;
-            if (live && idx < L) store_elem<BF16>(dx, base + idx, yh[k] * (g[k] - dot));
+            if (live && idx < L) store_elem<BF16>(dx, row * L + idx, yh[k] * (g[k] - dot));
         }
 }
 
