@@ -187,10 +187,17 @@ int softmax_group(int64_t L)
 
 // LDS bytes of one softmax block: the data span (+ up to 15 bytes of lead-in and
 // padding to a vector), then the codes span.
+// Row groups per block of the staged kernels, by measurement at the ViT-B/16
+// attention shape: the bf16 backward kernel gains 10 % from twice the bytes in
+// flight per block; the others lose from the lower block count and occupancy.
+constexpr int kFwdPasses = 1;
+template <bool BF16>
+constexpr int bwd_passes() { return BF16 ? 2 : 1; }
+
 template <bool BF16, int G>
-void softmax_lds(int L, int* data_bytes, int* codes_bytes, int* total_bytes)
+void softmax_lds(int L, int passes, int* data_bytes, int* codes_bytes, int* total_bytes)
 {
-    const int rpb = s2a::kSoftmaxBlock / G, es = BF16 ? 2 : 4;
+    const int rpb = passes * s2a::kSoftmaxBlock / G, es = BF16 ? 2 : 4;
     *data_bytes = ((rpb * L * es + 15 + 15) / 16) * 16;
     *codes_bytes = ((rpb * ((L + 1) / 2) + 15 + 15) / 16) * 16;
     *total_bytes = *data_bytes + *codes_bytes + 16;  // + the spare slot dead lanes write to
@@ -200,15 +207,15 @@ template <bool BF16, int G>
 int launch_softmax_fwd_g(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
                          hipStream_t st)
 {
-    const int rpb = s2a::kSoftmaxBlock / G;
+    const bool staged = aligned(x, 16) && aligned(y, 16) && aligned(codes, 16);
+    const int rpb = (staged ? kFwdPasses : 1) * s2a::kSoftmaxBlock / G;
     int64_t blocks = (rows + rpb - 1) / rpb;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     int data_bytes, codes_bytes, total;
-    softmax_lds<BF16, G>(L, &data_bytes, &codes_bytes, &total);
-    const bool staged = aligned(x, 16) && aligned(y, 16) && aligned(codes, 16);
+    softmax_lds<BF16, G>(L, kFwdPasses, &data_bytes, &codes_bytes, &total);
     return checked_launch([&] {
         if (staged)
-            s2a::softmax_fwd_staged<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
+            s2a::softmax_fwd_staged<BF16, G, kFwdPasses><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
                 x, y, codes, qp, rows, L, data_bytes, codes_bytes);
         else
             s2a::softmax_fwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
@@ -219,15 +226,15 @@ template <bool BF16, int G>
 int launch_softmax_bwd_g(const void* dy, const uint8_t* codes, const float* qp, void* dx,
                          int64_t rows, int L, hipStream_t st)
 {
-    const int rpb = s2a::kSoftmaxBlock / G;
+    const bool staged = aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 16);
+    const int rpb = (staged ? bwd_passes<BF16>() : 1) * s2a::kSoftmaxBlock / G;
     int64_t blocks = (rows + rpb - 1) / rpb;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     int data_bytes, codes_bytes, total;
-    softmax_lds<BF16, G>(L, &data_bytes, &codes_bytes, &total);
-    const bool staged = aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 16);
+    softmax_lds<BF16, G>(L, bwd_passes<BF16>(), &data_bytes, &codes_bytes, &total);
     return checked_launch([&] {
         if (staged)
-            s2a::softmax_bwd_staged<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
+            s2a::softmax_bwd_staged<BF16, G, bwd_passes<BF16>()><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
                 dy, codes, qp, dx, rows, L, data_bytes, codes_bytes);
         else
             s2a::softmax_bwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(

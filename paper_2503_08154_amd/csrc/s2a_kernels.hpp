@@ -844,7 +844,8 @@ __device__ __forceinline__ void lds_out(unsigned char* p, float v)
     if (BF16) *(uint16_t*)p = (uint16_t)pack_bf16(v, 0.0f); else *(float*)p = v;
 }
 
-template <bool BF16, int G>
+// PASSES = row groups per block: more bytes in flight per block, fewer blocks.
+template <bool BF16, int G, int PASSES>
 __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* x, void* y,
                                                                     uint8_t* codes,
                                                                     float* __restrict__ qparams,
@@ -852,20 +853,16 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
                                                                     int data_bytes, int codes_bytes)
 {
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr int RPB = kSoftmaxBlock / G;
+    constexpr int RPP = kSoftmaxBlock / G;           // rows per pass
+    constexpr int RPB = RPP * PASSES;        // rows per block
     extern __shared__ __align__(16) unsigned char lds[];
-    const int l = threadIdx.x % G, lrow = threadIdx.x / G;
+    const int l = threadIdx.x % G;
     const int64_t row0 = (int64_t)blockIdx.x * RPB;
     const int nrows = rows - row0 < RPB ? (int)(rows - row0) : RPB;
-    const bool live = lrow < nrows;
-    const int srow = live ? lrow : nrows - 1;  // dead lanes shadow the last real row
     const int rb = (L + 1) / 2;
     const int64_t xa = row0 * L * ES, xb = (row0 + nrows) * L * ES;
     const int64_t ca = row0 * rb, cb = (row0 + nrows) * rb;
     unsigned char* spare = lds + data_bytes + codes_bytes;
-    // this lane's element of slot 0, and the byte its pair shares, inside LDS
-    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + l) * ES;
-    unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
     const int klast = (L - 1) / G;            // the only slot that can be partly empty
     const int ilast = l + klast * G;          // this lane's element index in that slot
     const bool has_last = ilast < L;
@@ -874,6 +871,15 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
 
     stage_in<ES>(x, lds, xa, xb, rows * L * ES);
     __syncthreads();
+
+#pragma unroll 1
+    for (int pass = 0; pass < PASSES; ++pass) {
+    const int lrow = pass * RPP + (int)threadIdx.x / G;
+    const bool live = lrow < nrows;
+    const int srow = live ? lrow : nrows - 1;  // dead lanes shadow the last real row
+    // this lane's element of slot 0, and the byte its pair shares, inside LDS
+    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + l) * ES;
+    unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
 
     // pass 1: load, row maximum and minimum
     float v[kSoftmaxSlots];
@@ -903,12 +909,13 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
     vl = has_last ? exp_diff<BF16>(vl, m) : 0.0f;
     sum += (acc_t)vl;
     sum = group_sum<G>(sum);
-    const float inv = (float)((acc_t)1 / sum);
+    // reciprocals by v_rcp_f32 (1 ulp): a full division sequence costs a dozen instructions per lane
+    const float inv = BF16 ? __builtin_amdgcn_rcpf((float)sum) : (float)((acc_t)1 / sum);
     // y is monotone in x, so its extremes are the images of the row's extremes
     const float hi = exp_diff<BF16>(m, m) * inv;
     const float lo = exp_diff<BF16>(xmin, m) * inv;
-    const float scale = (hi - lo) / 15.0f;
-    const float inv_scale = scale > 0.0f ? 15.0f / (hi - lo) : 0.0f;
+    const float scale = (hi - lo) * (1.0f / 15.0f);
+    const float inv_scale = hi > lo ? 15.0f * __builtin_amdgcn_rcpf(hi - lo) : 0.0f;
     if (live && l == 0) {
         qparams[2 * (row0 + lrow)] = lo;
         qparams[2 * (row0 + lrow) + 1] = scale;
@@ -943,12 +950,13 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
         lds_out<BF16>(live && has_last ? lx + klast * G * ES : spare, yk);
         *(live && byte_in_row ? lc + klast * (G / 2) : spare) = (uint8_t)((c << own_shift) | (other << other_shift));
     }
+    }  // pass
     __syncthreads();
     stage_out<ES>(y, lds, xa, xb);
     stage_out<1>(codes, lds + data_bytes, ca, cb);
 }
 
-template <bool BF16, int G>
+template <bool BF16, int G, int PASSES>
 __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* dy,
                                                                     const uint8_t* codes,
                                                                     const float* __restrict__ qparams,
@@ -956,19 +964,16 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* 
                                                                     int data_bytes, int codes_bytes)
 {
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr int RPB = kSoftmaxBlock / G;
+    constexpr int RPP = kSoftmaxBlock / G;
+    constexpr int RPB = RPP * PASSES;
     extern __shared__ __align__(16) unsigned char lds[];
-    const int l = threadIdx.x % G, lrow = threadIdx.x / G;
+    const int l = threadIdx.x % G;
     const int64_t row0 = (int64_t)blockIdx.x * RPB;
     const int nrows = rows - row0 < RPB ? (int)(rows - row0) : RPB;
-    const bool live = lrow < nrows;
-    const int srow = live ? lrow : nrows - 1;
     const int rb = (L + 1) / 2;
     const int64_t xa = row0 * L * ES, xb = (row0 + nrows) * L * ES;
     const int64_t ca = row0 * rb, cb = (row0 + nrows) * rb;
     unsigned char* spare = lds + data_bytes + codes_bytes;
-    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + l) * ES;
-    const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
     const int klast = (L - 1) / G;
     const int ilast = l + klast * G;
     const bool has_last = ilast < L;
@@ -976,9 +981,17 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* 
 
     stage_in<ES>(dy, lds, xa, xb, rows * L * ES);
     stage_in<1>(codes, lds + data_bytes, ca, cb, rows * rb);
+    __syncthreads();
+
+#pragma unroll 1
+    for (int pass = 0; pass < PASSES; ++pass) {
+    const int lrow = pass * RPP + (int)threadIdx.x / G;
+    const bool live = lrow < nrows;
+    const int srow = live ? lrow : nrows - 1;
+    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + l) * ES;
+    const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
     const float lo = qparams[2 * (row0 + srow)];
     const float scale = qparams[2 * (row0 + srow) + 1];
-    __syncthreads();
 
     auto dequant = [&](uint32_t byte) { return __builtin_fmaf((float)((byte >> nib_shift) & 15u), scale, lo); };
     float yh[kSoftmaxSlots], g[kSoftmaxSlots];
@@ -1004,6 +1017,7 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* 
     for (int k = 0; k < kSoftmaxSlots - 1; ++k)
         if (k < klast) lds_out<BF16>(wx + k * xstep, yh[k] * (g[k] - dot));
     lds_out<BF16>(live && has_last ? lx + klast * G * ES : spare, yl * (gl - dot));
+    }  // pass
     __syncthreads();
     stage_out<ES>(dx, lds, xa, xb);
 }
