@@ -5,6 +5,8 @@
 
 #include <math.h>
 
+#include <type_traits>
+
 #include "s2a_kernels.hpp"
 
 namespace {
@@ -203,6 +205,33 @@ void softmax_lds(int L, int passes, int* data_bytes, int* codes_bytes, int* tota
     *total_bytes = *data_bytes + *codes_bytes + 16;  // + the spare slot dead lanes write to
 }
 
+// Slot buckets of the staged kernels (13 = 197-long rows with 16 lanes, 7 = 49 with 8, 9 = 257 with 32).
+template <bool BF16, int G, int SLOTS>
+void softmax_fwd_staged_launch(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
+                               unsigned blocks, int total, int data_bytes, int codes_bytes, hipStream_t st)
+{
+    s2a::softmax_fwd_staged<BF16, G, kFwdPasses, SLOTS><<<dim3(blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
+        x, y, codes, qp, rows, L, data_bytes, codes_bytes);
+}
+template <bool BF16, int G, int SLOTS>
+void softmax_bwd_staged_launch(const void* dy, const uint8_t* codes, const float* qp, void* dx, int64_t rows,
+                               int L, unsigned blocks, int total, int data_bytes, int codes_bytes, hipStream_t st)
+{
+    s2a::softmax_bwd_staged<BF16, G, bwd_passes<BF16>(), SLOTS><<<dim3(blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
+        dy, codes, qp, dx, rows, L, data_bytes, codes_bytes);
+}
+// Calls f.template operator()<SLOTS>() for the smallest bucket that holds `slots`.
+// Groups wider than 8 lanes only occur for rows that need at least 9 slots.
+template <int G, typename F>
+void with_slot_bucket(int slots, F f)
+{
+    if (G == 8 && slots <= 4) f(std::integral_constant<int, 4>{});
+    else if (G == 8 && slots <= 7) f(std::integral_constant<int, 7>{});
+    else if (slots <= 9) f(std::integral_constant<int, 9>{});
+    else if (slots <= 13) f(std::integral_constant<int, 13>{});
+    else f(std::integral_constant<int, 16>{});
+}
+
 template <bool BF16, int G>
 int launch_softmax_fwd_g(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
                          hipStream_t st)
@@ -215,8 +244,10 @@ int launch_softmax_fwd_g(const void* x, void* y, uint8_t* codes, float* qp, int6
     softmax_lds<BF16, G>(L, kFwdPasses, &data_bytes, &codes_bytes, &total);
     return checked_launch([&] {
         if (staged)
-            s2a::softmax_fwd_staged<BF16, G, kFwdPasses><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
-                x, y, codes, qp, rows, L, data_bytes, codes_bytes);
+            with_slot_bucket<G>((L - 1) / G + 1, [&](auto sc) {
+                softmax_fwd_staged_launch<BF16, G, decltype(sc)::value>(x, y, codes, qp, rows, L, (unsigned)blocks,
+                                                                        total, data_bytes, codes_bytes, st);
+            });
         else
             s2a::softmax_fwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
                 x, y, codes, qp, rows, L);
@@ -234,8 +265,10 @@ int launch_softmax_bwd_g(const void* dy, const uint8_t* codes, const float* qp, 
     softmax_lds<BF16, G>(L, bwd_passes<BF16>(), &data_bytes, &codes_bytes, &total);
     return checked_launch([&] {
         if (staged)
-            s2a::softmax_bwd_staged<BF16, G, bwd_passes<BF16>()><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
-                dy, codes, qp, dx, rows, L, data_bytes, codes_bytes);
+            with_slot_bucket<G>((L - 1) / G + 1, [&](auto sc) {
+                softmax_bwd_staged_launch<BF16, G, decltype(sc)::value>(dy, codes, qp, dx, rows, L, (unsigned)blocks,
+                                                                        total, data_bytes, codes_bytes, st);
+            });
         else
             s2a::softmax_bwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
                 dy, codes, qp, dx, rows, L);

@@ -845,7 +845,10 @@ __device__ __forceinline__ void lds_out(unsigned char* p, float v)
 }
 
 // PASSES = row groups per block: more bytes in flight per block, fewer blocks.
-template <bool BF16, int G, int PASSES>
+// SLOTS = slots compiled in (>= (L-1)/G + 1): the unrolled slot loops are turned
+// into selects by the compiler, so every compiled slot costs its arithmetic
+// whether the row reaches it or not; the launcher picks the smallest bucket.
+template <bool BF16, int G, int PASSES, int SLOTS>
 __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* x, void* y,
                                                                     uint8_t* codes,
                                                                     float* __restrict__ qparams,
@@ -882,10 +885,10 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
     unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
 
     // pass 1: load, row maximum and minimum
-    float v[kSoftmaxSlots];
+    float v[SLOTS];
     float m = ninf, xmin = pinf;
 #pragma unroll
-    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+    for (int k = 0; k < SLOTS - 1; ++k)
         if (k < klast) {
             v[k] = lds_in<BF16>(lx + k * G * ES);
             m = vmax(m, v[k]);
@@ -901,7 +904,7 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
     typedef typename std::conditional<BF16, float, double>::type acc_t;
     acc_t sum = 0;
 #pragma unroll
-    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+    for (int k = 0; k < SLOTS - 1; ++k)
         if (k < klast) {
             v[k] = exp_diff<BF16>(v[k], m);
             sum += (acc_t)v[k];
@@ -933,7 +936,7 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
     unsigned char* wc = live ? lc : spare;
     const int ystep = live ? G * ES : 0, cstep = live ? G / 2 : 0;
 #pragma unroll
-    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+    for (int k = 0; k < SLOTS - 1; ++k)
         if (k < klast) {
             const float yk = v[k] * inv;
             const uint32_t c = quantize(yk);
@@ -956,7 +959,7 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
     stage_out<1>(codes, lds + data_bytes, ca, cb);
 }
 
-template <bool BF16, int G, int PASSES>
+template <bool BF16, int G, int PASSES, int SLOTS>
 __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* dy,
                                                                     const uint8_t* codes,
                                                                     const float* __restrict__ qparams,
@@ -994,10 +997,10 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* 
     const float scale = qparams[2 * (row0 + srow) + 1];
 
     auto dequant = [&](uint32_t byte) { return __builtin_fmaf((float)((byte >> nib_shift) & 15u), scale, lo); };
-    float yh[kSoftmaxSlots], g[kSoftmaxSlots];
+    float yh[SLOTS], g[SLOTS];
     float dot = 0.0f;
 #pragma unroll
-    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+    for (int k = 0; k < SLOTS - 1; ++k)
         if (k < klast) {
             yh[k] = dequant(lc[k * (G / 2)]);
             g[k] = lds_in<BF16>(lx + k * G * ES);
@@ -1014,7 +1017,7 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* 
     unsigned char* wx = live ? lx : spare;
     const int xstep = live ? G * ES : 0;
 #pragma unroll
-    for (int k = 0; k < kSoftmaxSlots - 1; ++k)
+    for (int k = 0; k < SLOTS - 1; ++k)
         if (k < klast) lds_out<BF16>(wx + k * xstep, yh[k] * (g[k] - dot));
     lds_out<BF16>(live && has_last ? lx + klast * G * ES : spare, yl * (gl - dot));
     }  // pass
