@@ -135,6 +135,20 @@ int s2a_act_bwd_dyn(const void* dy, const uint8_t* codes, const float* qstate, v
                     int dtype, void* stream);
 
 /*
+ * SiLU / Swish with the same 4-bit scheme (GeLU paragraph, last sentence: the
+ * design "is also effective for similar non-parametric functions, such as SiLU
+ * and Swish"; the paper gives no constants).  SiLU(x) = x sigma(x) is the
+ * paper's GELU form x sigma(1.702 x) under x -> x / 1.702, so everything
+ * transfers by that substitution:
+ *   forward   y = x * sigma(x);  code = round((clip(x, -3.404, 3.404) + 3.404) * 15 / 6.808)
+ *   backward  dx = dy * (sigma(xh) + 0.22 sin(1.5 xh / 1.702)),  xh = -3.404 + code * 6.808/15
+ * Arguments, layout and errors as for s2a_act_fwd / s2a_act_bwd (fixed range
+ * only); needs s2a_qtable_init.
+ */
+int s2a_silu_fwd(const void* x, void* y, uint8_t* codes, int64_t n, int dtype, void* stream);
+int s2a_silu_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int dtype, void* stream);
+
+/*
  * ReLU with a 1-bit saved activation (Sec. 3.2, "ReLU layer": the derivative
  * is 0 or 1, so the mask x > 0 is all the backward pass needs).
  *   forward   y[i] = x[i] > 0 ? x[i] : 0;  bit i of `mask` = x[i] > 0

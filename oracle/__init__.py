@@ -65,6 +65,17 @@ def _load():
         lib.s2a_oracle_softmax_fwd.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp, d]
         lib.s2a_oracle_softmax_bwd.restype = i
         lib.s2a_oracle_softmax_bwd.argtypes = [vp, i, vp, vp, vp, i64, i64, vp]
+        for name in ("s2a_oracle_silu", "s2a_oracle_silu_deriv_approx"):
+            getattr(lib, name).restype = d
+            getattr(lib, name).argtypes = [d]
+        lib.s2a_oracle_silu_quantize.restype = i
+        lib.s2a_oracle_silu_quantize.argtypes = [d]
+        lib.s2a_oracle_silu_dequantize.restype = d
+        lib.s2a_oracle_silu_dequantize.argtypes = [i]
+        lib.s2a_oracle_silu_fwd.restype = i
+        lib.s2a_oracle_silu_fwd.argtypes = [vp, i, i64, vp, vp, vp, vp, d]
+        lib.s2a_oracle_silu_bwd.restype = i
+        lib.s2a_oracle_silu_bwd.argtypes = [vp, i, vp, i64, vp]
         lib.s2a_oracle_range.restype = i
         lib.s2a_oracle_range.argtypes = [vp, i, i64, vp, vp]
         lib.s2a_oracle_quantize_dyn.restype = i
@@ -257,4 +268,47 @@ def softmax_bwd(dy: np.ndarray, dtype: int, packed: np.ndarray, qmin: np.ndarray
                                         qscale.ctypes.data, rows, L, dx.ctypes.data)
     if rc != 0:
         raise ValueError("s2a_oracle_softmax_bwd rejected its arguments")
+    return dx
+
+
+# ---- SiLU / Swish (the GELU scheme under x -> x / 1.702) ----
+
+def silu(x: float) -> float:
+    return _load().s2a_oracle_silu(float(x))
+
+
+def silu_deriv_approx(x: float) -> float:
+    return _load().s2a_oracle_silu_deriv_approx(float(x))
+
+
+def silu_quantize(x: float) -> int:
+    return _load().s2a_oracle_silu_quantize(float(x))
+
+
+def silu_dequantize(q: int) -> float:
+    return _load().s2a_oracle_silu_dequantize(int(q))
+
+
+def silu_fwd(x: np.ndarray, dtype: int, band: float = 1e-6):
+    """Returns (y, code, packed, near) as fwd() does, for SiLU."""
+    x = _storage(x, dtype)
+    n = x.shape[0]
+    y = np.empty(n, np.float64)
+    code = np.empty(n, np.uint8)
+    packed = np.empty((n + 1) // 2, np.uint8)
+    near = np.empty(n, np.uint8)
+    if _load().s2a_oracle_silu_fwd(x.ctypes.data, dtype, n, y.ctypes.data, code.ctypes.data,
+                                   packed.ctypes.data, near.ctypes.data, float(band)) != 0:
+        raise ValueError("s2a_oracle_silu_fwd rejected its arguments")
+    return y, code, packed, near
+
+
+def silu_bwd(dy: np.ndarray, dtype: int, packed: np.ndarray) -> np.ndarray:
+    dy = _storage(dy, dtype)
+    n = dy.shape[0]
+    if packed.dtype != np.uint8 or packed.shape != ((n + 1) // 2,) or not packed.flags.c_contiguous:
+        raise TypeError("packed must be contiguous uint8 of length ceil(n/2)")
+    dx = np.empty(n, np.float64)
+    if _load().s2a_oracle_silu_bwd(dy.ctypes.data, dtype, packed.ctypes.data, n, dx.ctypes.data) != 0:
+        raise ValueError("s2a_oracle_silu_bwd rejected its arguments")
     return dx

@@ -375,3 +375,65 @@ int s2a_oracle_softmax_bwd(const void *dy, int dtype, const uint8_t *packed, con
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * SiLU / Swish (GeLU paragraph, last sentence: the design also serves "similar
+ * non-parametric functions, such as SiLU and Swish").  The paper gives no
+ * constants for it.  SiLU(x) = x sigma(x) is Eq. 10 under x -> x / 1.702
+ * (SiLU(x) = 1.702 * GELU(x / 1.702)), so the derivative of SiLU at x is the
+ * derivative of Eq. 10 at x / 1.702 and the paper's fit, range and bit width
+ * carry over by that substitution: derivative sigma(x) + 0.22 sin(1.5 x/1.702),
+ * clip to [-2*1.702, 2*1.702], 16 levels.  This reading is this build's.
+ *
+ * Pins (tests/test_oracle_silu_pins.py): a library SiLU and its automatic
+ * differentiation; exact agreement with the GELU functions above under the
+ * substitution.
+ * ---------------------------------------------------------------------- */
+#define ORACLE_SILU_CLIP (2.0 * 1.702)
+
+double s2a_oracle_silu(double x) { return x * logistic(x); }
+
+double s2a_oracle_silu_deriv_approx(double x) { return logistic(x) + 0.22 * sin(1.5 * x / 1.702); }
+
+static double silu_scale(void) { return (2.0 * ORACLE_SILU_CLIP) / (double)((1 << ORACLE_NBITS) - 1); }
+
+int s2a_oracle_silu_quantize(double x)
+{
+    double xc = fmin(fmax(x, -ORACLE_SILU_CLIP), ORACLE_SILU_CLIP);
+    return (int)nearbyint((xc + ORACLE_SILU_CLIP) / silu_scale());
+}
+
+double s2a_oracle_silu_dequantize(int q) { return (double)q * silu_scale() - ORACLE_SILU_CLIP; }
+
+int s2a_oracle_silu_fwd(const void *x, int dtype, int64_t n, double *y, uint8_t *code,
+                        uint8_t *packed, uint8_t *near, double band)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n < 0) return -1;
+    if (packed) memset(packed, 0, (size_t)((n + 1) / 2));
+    for (int64_t i = 0; i < n; ++i) {
+        double xi = load_elem(x, dtype, i);
+        int q = s2a_oracle_silu_quantize(xi);
+        if (y) y[i] = s2a_oracle_silu(xi);
+        if (code) code[i] = (uint8_t)q;
+        if (packed) packed[i / 2] |= (uint8_t)(q << (4 * (i & 1)));
+        if (near) {
+            double best = INFINITY;
+            for (int j = 0; j < 15; ++j) {
+                double d = fabs(xi - (-ORACLE_SILU_CLIP + ((double)j + 0.5) * silu_scale()));
+                if (d < best) best = d;
+            }
+            near[i] = (uint8_t)(best <= band);
+        }
+    }
+    return 0;
+}
+
+int s2a_oracle_silu_bwd(const void *dy, int dtype, const uint8_t *packed, int64_t n, double *dx)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n < 0) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        int q = (packed[i / 2] >> (4 * (i & 1))) & 0xF;
+        dx[i] = load_elem(dy, dtype, i) * s2a_oracle_silu_deriv_approx(s2a_oracle_silu_dequantize(q));
+    }
+    return 0;
+}

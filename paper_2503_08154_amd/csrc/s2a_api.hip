@@ -15,6 +15,7 @@ namespace {
 struct TableState {
     bool ready = false;
     s2a::QTable dev;   // fp32 derivative levels handed to kernels by value
+    s2a::QTable silu;  // the same for SiLU: Eq. 12 under x -> x / 1.702
     float xhat[16];
     float bounds[15];
 };
@@ -31,6 +32,10 @@ void build_table(TableState& t)
         double d = 1.0 / (1.0 + exp(-1.702 * xh)) + 0.22 * sin(1.5 * xh);
         t.xhat[k] = (float)xh;
         t.dev.d[k] = (float)d;
+        // SiLU(x) = 1.702 * GELU(x / 1.702): representatives 1.702 * xh, same derivative formula in xh
+        // written in the SiLU variable: sigma(xs) + 0.22 sin(1.5 xs / 1.702), xs = 1.702 * xh
+        double xs = 1.702 * xh;
+        t.silu.d[k] = (float)(1.0 / (1.0 + exp(-xs)) + 0.22 * sin(1.5 * xs / 1.702));
     }
     for (int j = 0; j < 15; ++j) t.bounds[j] = (float)(lo + step * ((double)j + 0.5));
     t.ready = true;
@@ -87,7 +92,7 @@ bool vector_grid(int64_t n, int64_t* nvec, unsigned* blocks)
     return true;
 }
 
-template <bool BF16, bool DYN>
+template <bool BF16, bool DYN, int ACT = s2a::kActGelu>
 int launch_fwd(const void* x, void* y, uint8_t* codes, const float* qs, int64_t n, hipStream_t st)
 {
     if (aligned(x, 16) && aligned(y, 16) && aligned(codes, 4)) {
@@ -95,18 +100,18 @@ int launch_fwd(const void* x, void* y, uint8_t* codes, const float* qs, int64_t 
         unsigned blocks;
         if (!vector_grid<BF16>(n, &nvec, &blocks)) return S2A_ERR_SIZE;
         return checked_launch([&] {
-            s2a::fwd_kernel<BF16, DYN><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+            s2a::fwd_kernel<BF16, DYN, ACT><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
                 (const s2a::u32x4*)x, (s2a::u32x4*)y, codes, qs, n, nvec);
         });
     }
     return checked_launch([&] {
-        s2a::fwd_kernel_unaligned<BF16, DYN><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(x, y, codes, qs, n);
+        s2a::fwd_kernel_unaligned<BF16, DYN, ACT><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(x, y, codes, qs, n);
     });
 }
 
 template <bool BF16, bool DYN>
 int launch_bwd(const void* dy, const uint8_t* codes, void* dx, const float* qs, int64_t n,
-               hipStream_t st)
+               hipStream_t st, const s2a::QTable& table = g_table.dev)
 {
     if (aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 4)) {
         int64_t nvec;
@@ -114,12 +119,12 @@ int launch_bwd(const void* dy, const uint8_t* codes, void* dx, const float* qs, 
         if (!vector_grid<BF16>(n, &nvec, &blocks)) return S2A_ERR_SIZE;
         return checked_launch([&] {
             s2a::bwd_kernel<BF16, DYN><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
-                (const s2a::u32x4*)dy, codes, (s2a::u32x4*)dx, g_table.dev, qs, n, nvec);
+                (const s2a::u32x4*)dy, codes, (s2a::u32x4*)dx, table, qs, n, nvec);
         });
     }
     return checked_launch([&] {
         s2a::bwd_kernel_unaligned<BF16, DYN><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(
-            dy, codes, dx, g_table.dev, qs, n);
+            dy, codes, dx, table, qs, n);
     });
 }
 
@@ -378,6 +383,24 @@ int s2a_act_bwd_dyn(const void* dy, const uint8_t* codes, const float* qstate, v
     hipStream_t st = (hipStream_t)stream;
     return dtype == S2A_BF16 ? launch_bwd<true, true>(dy, codes, dx, qstate, n, st)
                              : launch_bwd<false, true>(dy, codes, dx, qstate, n, st);
+}
+
+int s2a_silu_fwd(const void* x, void* y, uint8_t* codes, int64_t n, int dtype, void* stream)
+{
+    int rc = check_common(x, y, codes, n, dtype);
+    if (rc != S2A_OK || n == 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_fwd<true, false, s2a::kActSilu>(x, y, codes, nullptr, n, st)
+                             : launch_fwd<false, false, s2a::kActSilu>(x, y, codes, nullptr, n, st);
+}
+
+int s2a_silu_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int dtype, void* stream)
+{
+    int rc = check_common(dy, codes, dx, n, dtype);
+    if (rc != S2A_OK || n == 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_bwd<true, false>(dy, codes, dx, nullptr, n, st, g_table.silu)
+                             : launch_bwd<false, false>(dy, codes, dx, nullptr, n, st, g_table.silu);
 }
 
 int s2a_relu_fwd(const void* x, void* y, uint8_t* mask, int64_t n, int dtype, void* stream)

@@ -43,11 +43,24 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-// 1.702 * log2(e) = 2.45546695959301560..., split so that kKhi + kKlo carries
-// 48 bits of the product (the fp32 path needs more than one fp32 of it).
-constexpr double kKd = 1.702 * 1.4426950408889634074;
-constexpr float kKhi = (float)kKd;
-constexpr float kKlo = (float)(kKd - (double)kKhi);
+// The activation is x * sigma(a x): a = 1.702 for the paper's GELU (Eq. 10),
+// a = 1 for SiLU / Swish, which the GeLU paragraph names as covered by the same
+// design.  Under the substitution x -> x / 1.702 SiLU(x) = 1.702 * GELU(x/1.702),
+// so its derivative at x is Eq. 11 at x / 1.702, the sine fit becomes
+// sigma(x) + 0.22 sin(1.5 x / 1.702), and the clip range becomes +-2 * 1.702.
+enum { kActGelu = 0, kActSilu = 1 };
+template <int ACT>
+struct Act {
+    static constexpr double slope = ACT == kActGelu ? 1.702 : 1.0;
+    static constexpr double clip = ACT == kActGelu ? 2.0 : 2.0 * 1.702;
+    // slope * log2(e), split so that hi + lo carries 48 bits of the product
+    // (the fp32 path needs more than one fp32 of it)
+    static constexpr double kd = slope * 1.4426950408889634074;
+    static constexpr float khi = (float)kd;
+    static constexpr float klo = (float)(kd - (double)khi);
+    // binning: code = floor(x * 7.5/clip + 8)   (3.75 and 8, both exact, for GELU)
+    static constexpr float bin_scale = (float)(7.5 / clip);
+};
 constexpr float kLn2 = 0.69314718055994530942f;
 
 // ---------------------------------------------------------------- Eq. 10 ---
@@ -58,9 +71,10 @@ constexpr float kLn2 = 0.69314718055994530942f;
 // That keeps the quotient representable for x down to about -65, where y has
 // already dropped below the smallest bf16 denormal, instead of overflowing at
 // x = -52 where y is still a normal number.
+template <int ACT>
 __device__ __forceinline__ float gelu_fast(float x)
 {
-    float u = __builtin_fmaf(x, -kKhi, -32.0f);
+    float u = __builtin_fmaf(x, -Act<ACT>::khi, -32.0f);
     float e = __builtin_amdgcn_exp2f(u);             // v_exp_f32
     float r = __builtin_amdgcn_rcpf(e + 0x1p-32f);   // v_rcp_f32, = 2^32 sigma
     return x * (r * 0x1p-32f);
@@ -77,12 +91,13 @@ __device__ __forceinline__ float gelu_fast(float x)
 //  - |x| is capped at 128 for the exponent only (beyond that sigma is exactly
 //    0 or 1 in fp32); the final product uses x itself, so +-inf and NaN behave
 //    as the formula says: y(+inf) = +inf, y(-inf) = NaN, y(NaN) = NaN.
+template <int ACT>
 __device__ __forceinline__ float gelu_accurate(float x)
 {
     float xs = __builtin_amdgcn_fmed3f(x, -128.0f, 128.0f);
-    float uh = xs * -kKhi;
-    float ul = __builtin_fmaf(xs, -kKhi, -uh);
-    ul = __builtin_fmaf(xs, -kKlo, ul);
+    float uh = xs * -Act<ACT>::khi;
+    float ul = __builtin_fmaf(xs, -Act<ACT>::khi, -uh);
+    ul = __builtin_fmaf(xs, -Act<ACT>::klo, ul);
     bool big = uh > 64.0f;
     float e = __builtin_amdgcn_exp2f(uh - (big ? 64.0f : 0.0f));
     e = e * __builtin_fmaf(ul, kLn2, 1.0f);  // a product, so that e = +inf stays +inf
@@ -112,9 +127,10 @@ __device__ __forceinline__ uint32_t bin_affine(float x, float scale, float offse
     return c < 15u ? c : 15u;
 }
 
-// Fixed range: lo = -2, hi = 2 (the clip limits), scale = 3.75, offset = 8.
+// Fixed range: lo = -clip, hi = clip (the clip limits): scale = 7.5/clip, offset = 8.
+template <int ACT>
 struct BinFixed {
-    __device__ __forceinline__ uint32_t operator()(float x) const { return bin_affine(x, 3.75f, 8.0f); }
+    __device__ __forceinline__ uint32_t operator()(float x) const { return bin_affine(x, Act<ACT>::bin_scale, 8.0f); }
 };
 // Measured range: scale and offset prepared by range_finalize_kernel.
 struct BinRange {
@@ -167,8 +183,8 @@ __device__ __forceinline__ void store_elem(void* p, int64_t i, float v)
 {
     if (BF16) store_elem_bf16(p, i, v); else store_elem_f32(p, i, v);
 }
-template <bool BF16>
-__device__ __forceinline__ float gelu(float x) { return BF16 ? gelu_fast(x) : gelu_accurate(x); }
+template <bool BF16, int ACT>
+__device__ __forceinline__ float gelu(float x) { return BF16 ? gelu_fast<ACT>(x) : gelu_accurate<ACT>(x); }
 
 // Streaming memory access.  Loads carry the non-temporal hint (nt).  Stores
 // carry "sc0 sc1 nt": written through to memory at system scope and not kept
@@ -209,7 +225,7 @@ __device__ __forceinline__ void store_codes(uint8_t* codes, int64_t v, uint32_t 
 // ------------------------------------------------- element-wise pieces ----
 
 // Elements [first, n) with first even: one code byte per pair, pad nibble 0.
-template <bool BF16, typename Bin>
+template <bool BF16, int ACT, typename Bin>
 __device__ __forceinline__ void fwd_pairs(const void* x, void* y, uint8_t* codes, Bin bin,
                                           int64_t first, int64_t n, int64_t pair0,
                                           int64_t pair_stride)
@@ -219,11 +235,11 @@ __device__ __forceinline__ void fwd_pairs(const void* x, void* y, uint8_t* codes
         int64_t i = first + 2 * p;
         float a = load_elem<BF16>(x, i);
         uint32_t byte = bin(a);
-        store_elem<BF16>(y, i, gelu<BF16>(a));
+        store_elem<BF16>(y, i, gelu<BF16, ACT>(a));
         if (i + 1 < n) {
             float b = load_elem<BF16>(x, i + 1);
             byte |= bin(b) << 4;
-            store_elem<BF16>(y, i + 1, gelu<BF16>(b));
+            store_elem<BF16>(y, i + 1, gelu<BF16, ACT>(b));
         }
         codes[i / 2] = (uint8_t)byte;
     }
@@ -248,7 +264,7 @@ __device__ __forceinline__ void bwd_pairs(const void* dy, const uint8_t* codes, 
 // ------------------------------------------------------------- forward ----
 
 // One vector of 8 bf16: y bits in place, returns the 8 packed codes.
-template <bool BF16, typename Bin>
+template <bool BF16, int ACT, typename Bin>
 __device__ __forceinline__ uint32_t fwd_vector(u32x4& v, Bin bin)
 {
     uint32_t acc = 0;
@@ -258,14 +274,14 @@ __device__ __forceinline__ uint32_t fwd_vector(u32x4& v, Bin bin)
             float a = bf16_lo(v[j]), b = bf16_hi(v[j]);
             acc = push_nibble(acc, bin(a));
             acc = push_nibble(acc, bin(b));
-            v[j] = pack_bf16(gelu_fast(a), gelu_fast(b));
+            v[j] = pack_bf16(gelu_fast<ACT>(a), gelu_fast<ACT>(b));
         }
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float a = as_f32(v[j]);
             acc = push_nibble(acc, bin(a));
-            v[j] = as_u32(gelu_accurate(a));
+            v[j] = as_u32(gelu_accurate<ACT>(a));
         }
         acc >>= 16;  // 4 codes -> low 16 bits
     }
@@ -293,38 +309,38 @@ constexpr int kQsMin = 2, kQsScale = 3, kQsInv = 4, kQsOff = 5, kQsTable = 16, k
 //   DYN    false: fixed range [-2, 2]; true: range read from qs (see above)
 //   nvec   number of full vectors, n / EPV
 //   grid   ceil((nvec + (n % EPV != 0)) / kWave) blocks of kWave lanes
-template <bool BF16, bool DYN>
+template <bool BF16, bool DYN, int ACT>
 __global__ __launch_bounds__(kWave) void fwd_kernel(const u32x4* x, u32x4* y,
                                                     uint8_t* __restrict__ codes,
                                                     const float* __restrict__ qs, int64_t n,
                                                     int64_t nvec)
 {
     constexpr int EPV = BF16 ? 8 : 4;
-    typedef typename std::conditional<DYN, BinRange, BinFixed>::type Bin;
+    typedef typename std::conditional<DYN, BinRange, BinFixed<ACT>>::type Bin;
     Bin bin;
     if constexpr (DYN) bin = BinRange{qs[kQsInv], qs[kQsOff]};
     const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
     if (i < nvec) {
         u32x4 v = stream_load128(x + i);
-        uint32_t c = fwd_vector<BF16>(v, bin);
+        uint32_t c = fwd_vector<BF16, ACT>(v, bin);
         stream_store128(y + i, v);
         store_codes<BF16>(codes, i, c);
     } else if (i == nvec) {  // one lane finishes the n % EPV leftover elements
-        fwd_pairs<BF16>(x, y, codes, bin, nvec * EPV, n, 0, 1);
+        fwd_pairs<BF16, ACT>(x, y, codes, bin, nvec * EPV, n, 0, 1);
     }
 }
 
 // Any alignment: one lane per code byte, grid-stride.
-template <bool BF16, bool DYN>
+template <bool BF16, bool DYN, int ACT>
 __global__ __launch_bounds__(kBlock) void fwd_kernel_unaligned(const void* x, void* y,
                                                                uint8_t* codes,
                                                                const float* __restrict__ qs,
                                                                int64_t n)
 {
-    typedef typename std::conditional<DYN, BinRange, BinFixed>::type Bin;
+    typedef typename std::conditional<DYN, BinRange, BinFixed<ACT>>::type Bin;
     Bin bin;
     if constexpr (DYN) bin = BinRange{qs[kQsInv], qs[kQsOff]};
-    fwd_pairs<BF16>(x, y, codes, bin, 0, n, (int64_t)blockIdx.x * kBlock + threadIdx.x,
+    fwd_pairs<BF16, ACT>(x, y, codes, bin, 0, n, (int64_t)blockIdx.x * kBlock + threadIdx.x,
                     (int64_t)gridDim.x * kBlock);
 }
 

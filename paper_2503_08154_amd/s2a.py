@@ -26,7 +26,7 @@ QSTATE_FLOATS = 544
 SOFTMAX_MAX_L = 1024
 
 EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd",
-           "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_relu_fwd", "s2a_relu_bwd",
+           "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_silu_fwd", "s2a_silu_bwd", "s2a_relu_fwd", "s2a_relu_bwd",
            "s2a_softmax_fwd", "s2a_softmax_bwd", "s2a_strerror")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libs2a.so")
@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
         l.s2a_act_fwd_dyn.argtypes = [vp, vp, vp, vp, i64, i, vp]
         l.s2a_act_bwd_dyn.restype = i
         l.s2a_act_bwd_dyn.argtypes = [vp, vp, vp, vp, i64, i, vp]
+        l.s2a_silu_fwd.restype = i
+        l.s2a_silu_fwd.argtypes = [vp, vp, vp, i64, i, vp]
+        l.s2a_silu_bwd.restype = i
+        l.s2a_silu_bwd.argtypes = [vp, vp, vp, i64, i, vp]
         l.s2a_relu_fwd.restype = i
         l.s2a_relu_fwd.argtypes = [vp, vp, vp, i64, i, vp]
         l.s2a_relu_bwd.restype = i
@@ -154,4 +158,18 @@ def softmax_bwd(dy: int, codes: int, qparams: int, dx: int, rows: int, L: int, d
     rc = lib().s2a_softmax_bwd(dy, codes, qparams, dx, int(rows), int(L), int(dtype), stream)
     if check and rc != OK:
         raise S2AError(rc, "s2a_softmax_bwd")
+    return rc
+
+
+def silu_fwd(x: int, y: int, codes: int, n: int, dtype: int, stream: int = 0, check: bool = True) -> int:
+    rc = lib().s2a_silu_fwd(x, y, codes, int(n), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_silu_fwd")
+    return rc
+
+
+def silu_bwd(dy: int, codes: int, dx: int, n: int, dtype: int, stream: int = 0, check: bool = True) -> int:
+    rc = lib().s2a_silu_bwd(dy, codes, dx, int(n), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_silu_bwd")
     return rc
