@@ -76,6 +76,14 @@ def _load():
         lib.s2a_oracle_silu_fwd.argtypes = [vp, i, i64, vp, vp, vp, vp, d]
         lib.s2a_oracle_silu_bwd.restype = i
         lib.s2a_oracle_silu_bwd.argtypes = [vp, i, vp, i64, vp]
+        lib.s2a_oracle_cap_fwd.restype = i
+        lib.s2a_oracle_cap_fwd.argtypes = [vp, i, i64, i, vp]
+        lib.s2a_oracle_cap_bwd.restype = i
+        lib.s2a_oracle_cap_bwd.argtypes = [vp, i, i64, i, vp]
+        lib.s2a_oracle_lrp_fwd.restype = i
+        lib.s2a_oracle_lrp_fwd.argtypes = [vp, i, vp, vp, i64, i64, i64, i, vp]
+        lib.s2a_oracle_lrp_bwd.restype = i
+        lib.s2a_oracle_lrp_bwd.argtypes = [vp, i, vp, vp, i64, i64, i64, i, vp, vp]
         lib.s2a_oracle_range.restype = i
         lib.s2a_oracle_range.argtypes = [vp, i, i64, vp, vp]
         lib.s2a_oracle_quantize_dyn.restype = i
@@ -312,3 +320,54 @@ def silu_bwd(dy: np.ndarray, dtype: int, packed: np.ndarray) -> np.ndarray:
     if _load().s2a_oracle_silu_bwd(dy.ctypes.data, dtype, packed.ctypes.data, n, dx.ctypes.data) != 0:
         raise ValueError("s2a_oracle_silu_bwd rejected its arguments")
     return dx
+
+
+# ---- Channel Average Pooling (Eq. 5) and Low-Rank Prompt (Eq. 3-4) ----
+
+def cap_fwd(x: np.ndarray, dtype: int, r: int) -> np.ndarray:
+    x = _storage(x, dtype)
+    if x.shape[0] % r:
+        raise ValueError("length must be a multiple of r")
+    y = np.empty(x.shape[0] // r, np.float64)
+    if _load().s2a_oracle_cap_fwd(x.ctypes.data, dtype, y.shape[0], int(r), y.ctypes.data) != 0:
+        raise ValueError("s2a_oracle_cap_fwd rejected its arguments")
+    return y
+
+
+def cap_bwd(dy: np.ndarray, dtype: int, r: int) -> np.ndarray:
+    dy = _storage(dy, dtype)
+    dx = np.empty(dy.shape[0] * r, np.float64)
+    if _load().s2a_oracle_cap_bwd(dy.ctypes.data, dtype, dy.shape[0], int(r), dx.ctypes.data) != 0:
+        raise ValueError("s2a_oracle_cap_bwd rejected its arguments")
+    return dx
+
+
+def _f32(a, shape):
+    a = np.ascontiguousarray(a, np.float32)
+    if a.shape != shape:
+        raise ValueError(f"expected shape {shape}")
+    return a
+
+
+def lrp_fwd(x: np.ndarray, dtype: int, A: np.ndarray, B: np.ndarray, batch: int, N: int, C: int) -> np.ndarray:
+    x = _storage(x, dtype)
+    r = A.shape[1]
+    A, B = _f32(A, (N, r)), _f32(B, (r, C))
+    if x.shape[0] != batch * N * C:
+        raise ValueError("x must hold batch*N*C elements")
+    y = np.empty(batch * N * C, np.float64)
+    if _load().s2a_oracle_lrp_fwd(x.ctypes.data, dtype, A.ctypes.data, B.ctypes.data, batch, N, C, r, y.ctypes.data) != 0:
+        raise ValueError("s2a_oracle_lrp_fwd rejected its arguments")
+    return y
+
+
+def lrp_bwd(dy: np.ndarray, dtype: int, A: np.ndarray, B: np.ndarray, batch: int, N: int, C: int):
+    dy = _storage(dy, dtype)
+    r = A.shape[1]
+    A, B = _f32(A, (N, r)), _f32(B, (r, C))
+    dA = np.empty((N, r), np.float64)
+    dB = np.empty((r, C), np.float64)
+    if _load().s2a_oracle_lrp_bwd(dy.ctypes.data, dtype, A.ctypes.data, B.ctypes.data, batch, N, C, r,
+                                  dA.ctypes.data, dB.ctypes.data) != 0:
+        raise ValueError("s2a_oracle_lrp_bwd rejected its arguments")
+    return dA, dB

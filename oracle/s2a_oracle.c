@@ -437,3 +437,75 @@ int s2a_oracle_silu_bwd(const void *dy, int dtype, const uint8_t *packed, int64_
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Channel Average Pooling (Sec. 3.1, "Lite Side Branch" paragraph, Eq. 5):
+ * y_k = (1/r) sum_{j<r} x_{k r + j} along the channel axis, and
+ * dL/dx_{k r + j} = dL/dy_k / r.  Channels are contiguous and C is a multiple
+ * of r, so on the flat tensor output m averages inputs m*r .. m*r + r - 1.
+ *
+ * Pins (tests/test_oracle_cap_lrp_pins.py): a library average pooling and its
+ * automatic differentiation; the adjoint identity <CAP x, g> = <x, CAP^T g>.
+ * ---------------------------------------------------------------------- */
+int s2a_oracle_cap_fwd(const void *x, int dtype, int64_t n_out, int r, double *y)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n_out < 0 || r < 1) return -1;
+    for (int64_t m = 0; m < n_out; ++m) {
+        double acc = 0.0;
+        for (int j = 0; j < r; ++j) acc += load_elem(x, dtype, m * r + j);
+        y[m] = acc / (double)r;
+    }
+    return 0;
+}
+
+int s2a_oracle_cap_bwd(const void *dy, int dtype, int64_t n_out, int r, double *dx)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || n_out < 0 || r < 1) return -1;
+    for (int64_t m = 0; m < n_out; ++m)
+        for (int j = 0; j < r; ++j) dx[m * r + j] = load_elem(dy, dtype, m) / (double)r;
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Low-Rank Prompt (Sec. 3.1, "Low-Rank Prompt (LRP)" paragraph, Eq. 3-4):
+ * y = x + A B with A in R^{N x r}, B in R^{r x C}; dL/dx = dL/dy,
+ * dL/dA = dL/dy B^T, dL/dB = A^T dL/dy.  x holds `batch` samples of N x C
+ * (row-major), and the same prompt A B is added to each, so the parameter
+ * gradients sum over the batch.  A and B are fp32 (they are trained
+ * parameters); x, y, dy use the storage type.
+ *
+ * Pins: a library matmul for the forward pass and automatic differentiation
+ * for the three gradients.
+ * ---------------------------------------------------------------------- */
+int s2a_oracle_lrp_fwd(const void *x, int dtype, const float *A, const float *B, int64_t batch,
+                       int64_t N, int64_t C, int r, double *y)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || batch < 0 || N < 0 || C < 0 || r < 0) return -1;
+    for (int64_t b = 0; b < batch; ++b)
+        for (int64_t i = 0; i < N; ++i)
+            for (int64_t c = 0; c < C; ++c) {
+                double p = 0.0;
+                for (int k = 0; k < r; ++k) p += (double)A[i * r + k] * (double)B[(int64_t)k * C + c];
+                y[(b * N + i) * C + c] = load_elem(x, dtype, (b * N + i) * C + c) + p;
+            }
+    return 0;
+}
+
+/* dA [N x r], dB [r x C]; dL/dx = dL/dy needs no arithmetic. */
+int s2a_oracle_lrp_bwd(const void *dy, int dtype, const float *A, const float *B, int64_t batch,
+                       int64_t N, int64_t C, int r, double *dA, double *dB)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || batch < 0 || N < 0 || C < 0 || r < 0) return -1;
+    for (int64_t i = 0; i < N * r; ++i) dA[i] = 0.0;
+    for (int64_t i = 0; i < (int64_t)r * C; ++i) dB[i] = 0.0;
+    for (int64_t b = 0; b < batch; ++b)
+        for (int64_t i = 0; i < N; ++i)
+            for (int64_t c = 0; c < C; ++c) {
+                double g = load_elem(dy, dtype, (b * N + i) * C + c);
+                for (int k = 0; k < r; ++k) {
+                    dA[i * r + k] += g * (double)B[(int64_t)k * C + c];
+                    dB[(int64_t)k * C + c] += (double)A[i * r + k] * g;
+                }
+            }
+    return 0;
+}
