@@ -185,6 +185,22 @@ int s2a_softmax_fwd(const void* x, void* y, uint8_t* codes, float* qparams, int6
 int s2a_softmax_bwd(const void* dy, const uint8_t* codes, const float* qparams, void* dx,
                     int64_t rows, int64_t L, int dtype, void* stream);
 
+/*
+ * Channel Average Pooling (Sec. 3.1, "Lite Side Branch" paragraph, Eq. 5), the
+ * parameter-free connector between the backbone and the side branch:
+ *   forward   y[m] = (1/r) * sum_{j<r} x[m*r + j]
+ *   backward  dx[m*r + j] = dy[m] / r
+ * Channels are contiguous, so m runs over all (token, channel-group) pairs of
+ * the flat tensor.  Nothing is saved for backward.
+ *   x, dx   device, n_out * r elements of `dtype`
+ *   y, dy   device, n_out elements of `dtype`
+ *   r       compression factor, a power of two in 2..64 (else S2A_ERR_SIZE);
+ *           the paper's experiments use 8
+ * x (dx) 16-byte aligned takes the vector kernel.  Needs no s2a_qtable_init.
+ */
+int s2a_cap_fwd(const void* x, void* y, int64_t n_out, int r, int dtype, void* stream);
+int s2a_cap_bwd(const void* dy, void* dx, int64_t n_out, int r, int dtype, void* stream);
+
 /* Static, NUL-terminated description of a return code.  Never NULL. */
 const char* s2a_strerror(int code);
 

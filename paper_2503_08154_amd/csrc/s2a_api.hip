@@ -314,6 +314,56 @@ int check_softmax(const void* a, const void* b, const void* c, const void* d, in
     return S2A_OK;
 }
 
+template <bool BF16, int R>
+int launch_cap_g(bool fwd, const void* in, void* out, int64_t n_out, hipStream_t st)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    const int64_t n_in = n_out * R;
+    const int64_t nvec = n_in / EPV;
+    const int64_t slots = nvec + (n_in % EPV != 0);
+    const int64_t blocks = (slots + s2a::kWave - 1) / s2a::kWave;
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    return checked_launch([&] {
+        if (fwd)
+            s2a::cap_fwd_kernel<BF16, R><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(
+                (const s2a::u32x4*)in, out, n_in, nvec);
+        else
+            s2a::cap_bwd_kernel<BF16, R><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(
+                in, (s2a::u32x4*)out, n_in, nvec);
+    });
+}
+
+// `wide` is the r-times larger tensor (x in forward, dx in backward): it decides the vector path.
+template <bool BF16>
+int launch_cap(bool fwd, const void* in, void* out, const void* wide, int64_t n_out, int r, hipStream_t st)
+{
+    if (aligned(wide, 16)) {
+        switch (r) {
+            case 2: return launch_cap_g<BF16, 2>(fwd, in, out, n_out, st);
+            case 4: return launch_cap_g<BF16, 4>(fwd, in, out, n_out, st);
+            case 8: return launch_cap_g<BF16, 8>(fwd, in, out, n_out, st);
+            case 16: return launch_cap_g<BF16, 16>(fwd, in, out, n_out, st);
+            case 32: return launch_cap_g<BF16, 32>(fwd, in, out, n_out, st);
+            case 64: return launch_cap_g<BF16, 64>(fwd, in, out, n_out, st);
+            default: return S2A_ERR_SIZE;
+        }
+    }
+    return checked_launch([&] {
+        if (fwd)
+            s2a::cap_fwd_kernel_unaligned<BF16><<<dim3(pair_grid(2 * n_out)), dim3(s2a::kBlock), 0, st>>>(in, out, n_out, r);
+        else
+            s2a::cap_bwd_kernel_unaligned<BF16><<<dim3(pair_grid(2 * n_out)), dim3(s2a::kBlock), 0, st>>>(in, out, n_out, r);
+    });
+}
+
+int check_cap(const void* a, const void* b, int64_t n_out, int r, int dtype)
+{
+    if (dtype != S2A_F32 && dtype != S2A_BF16) return S2A_ERR_DTYPE;
+    if (n_out < 0 || r < 2 || r > 64 || (r & (r - 1)) != 0) return S2A_ERR_SIZE;
+    if (n_out > 0 && (!a || !b)) return S2A_ERR_NULL;
+    return S2A_OK;
+}
+
 static_assert(s2a::kQsFloats == S2A_QSTATE_FLOATS, "header and kernels disagree on the qstate size");
 
 }  // namespace
@@ -439,6 +489,24 @@ int s2a_softmax_bwd(const void* dy, const uint8_t* codes, const float* qparams, 
     hipStream_t st = (hipStream_t)stream;
     return dtype == S2A_BF16 ? launch_softmax_bwd<true>(dy, codes, qparams, dx, rows, (int)L, st)
                              : launch_softmax_bwd<false>(dy, codes, qparams, dx, rows, (int)L, st);
+}
+
+int s2a_cap_fwd(const void* x, void* y, int64_t n_out, int r, int dtype, void* stream)
+{
+    int rc = check_cap(x, y, n_out, r, dtype);
+    if (rc != S2A_OK || n_out == 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_cap<true>(true, x, y, x, n_out, r, st)
+                             : launch_cap<false>(true, x, y, x, n_out, r, st);
+}
+
+int s2a_cap_bwd(const void* dy, void* dx, int64_t n_out, int r, int dtype, void* stream)
+{
+    int rc = check_cap(dy, dx, n_out, r, dtype);
+    if (rc != S2A_OK || n_out == 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    return dtype == S2A_BF16 ? launch_cap<true>(false, dy, dx, dx, n_out, r, st)
+                             : launch_cap<false>(false, dy, dx, dx, n_out, r, st);
 }
 
 const char* s2a_strerror(int code)

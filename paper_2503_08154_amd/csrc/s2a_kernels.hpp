@@ -1147,4 +1147,128 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_kernel(const void* 
         }
 }
 
+// --------------------------------------- Channel Average Pooling ----------
+//
+// Sec. 3.1, "Lite Side Branch" paragraph, Eq. 5: y_k = (1/r) sum_{j<r} x_{kr+j}
+// along the contiguous channel axis; dL/dx_{kr+j} = dL/dy_k / r.  Parameter
+// free and activation free: backward needs only dL/dy and r.  On the flat
+// tensor, output m averages inputs m*R .. m*R + R - 1 (R a power of two, 2..64).
+// Streaming skeleton as above: single-wave blocks, one 16-byte vector of x (of
+// dx) per lane.  R <= EPV: a lane produces EPV/R outputs; R > EPV: R/EPV
+// neighbouring lanes add up by DPP moves and the first of them stores.
+// Bytes per input element: e + e/R in either direction.
+
+template <bool BF16>
+__device__ __forceinline__ void unpack_vector(const u32x4& v, float* f)
+{
+    if (BF16) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f[2 * j] = bf16_lo(v[j]);
+            f[2 * j + 1] = bf16_hi(v[j]);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f[j] = as_f32(v[j]);
+    }
+}
+
+template <bool BF16, int R>
+__global__ __launch_bounds__(kWave) void cap_fwd_kernel(const u32x4* x, void* y, int64_t n_in,
+                                                        int64_t nvec)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    constexpr float kInv = 1.0f / (float)R;
+    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    if constexpr (R <= EPV) {
+        constexpr int OUT = EPV / R;  // outputs per lane
+        if (i < nvec) {
+            float f[EPV], o[OUT];
+            unpack_vector<BF16>(stream_load128(x + i), f);
+#pragma unroll
+            for (int q = 0; q < OUT; ++q) {
+                float acc = f[q * R];
+#pragma unroll
+                for (int j = 1; j < R; ++j) acc += f[q * R + j];
+                o[q] = acc * kInv;
+            }
+#pragma unroll
+            for (int q = 0; q < OUT; ++q) store_elem<BF16>(y, i * OUT + q, o[q]);
+        } else if (i == nvec) {  // leftover groups past the last full vector
+            for (int64_t m = nvec * OUT; m < n_in / R; ++m) {
+                float acc = 0.0f;
+                for (int j = 0; j < R; ++j) acc += load_elem<BF16>(x, m * R + j);
+                store_elem<BF16>(y, m, acc * kInv);
+            }
+        }
+    } else {
+        constexpr int K = R / EPV;  // lanes per output, 2..16: stays inside a DPP row
+        // every lane takes part in the DPP moves; lanes past the end recompute the last vector
+        float f[EPV];
+        unpack_vector<BF16>(stream_load128(x + (i < nvec ? i : nvec - 1)), f);
+        float acc = f[0];
+#pragma unroll
+        for (int j = 1; j < EPV; ++j) acc += f[j];
+        acc += dpp_move<kDppXor1>(acc);
+        if (K >= 4) acc += dpp_move<kDppXor2>(acc);
+        if (K >= 8) acc += dpp_move<kDppHalfMirror>(acc);
+        if (K >= 16) acc += dpp_move<kDppMirror>(acc);
+        if (i < nvec && (threadIdx.x % K) == 0) store_elem<BF16>(y, i / K, acc * kInv);
+    }
+}
+
+template <bool BF16, int R>
+__global__ __launch_bounds__(kWave) void cap_bwd_kernel(const void* dy, u32x4* dx, int64_t n_in,
+                                                        int64_t nvec)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    constexpr float kInv = 1.0f / (float)R;
+    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    if (i < nvec) {
+        float f[EPV];
+        if constexpr (R >= EPV) {
+            const float g = load_elem<BF16>(dy, i * EPV / R) * kInv;
+#pragma unroll
+            for (int j = 0; j < EPV; ++j) f[j] = g;
+        } else {
+            constexpr int OUT = EPV / R;
+#pragma unroll
+            for (int q = 0; q < OUT; ++q) {
+                const float g = load_elem<BF16>(dy, i * OUT + q) * kInv;
+#pragma unroll
+                for (int j = 0; j < R; ++j) f[q * R + j] = g;
+            }
+        }
+        u32x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = BF16 ? pack_bf16(f[2 * j], f[2 * j + 1]) : as_u32(f[j]);
+        stream_store128(dx + i, v);
+    } else if (i == nvec) {
+        for (int64_t e = nvec * EPV; e < n_in; ++e) store_elem<BF16>(dx, e, load_elem<BF16>(dy, e / R) * kInv);
+    }
+}
+
+// Any alignment: one lane per output element, grid-stride.
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void cap_fwd_kernel_unaligned(const void* x, void* y,
+                                                                   int64_t n_out, int r)
+{
+    const float inv = 1.0f / (float)r;
+    for (int64_t m = (int64_t)blockIdx.x * kBlock + threadIdx.x; m < n_out; m += (int64_t)gridDim.x * kBlock) {
+        float acc = 0.0f;
+        for (int j = 0; j < r; ++j) acc += load_elem<BF16>(x, m * r + j);
+        store_elem<BF16>(y, m, acc * inv);
+    }
+}
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void cap_bwd_kernel_unaligned(const void* dy, void* dx,
+                                                                   int64_t n_out, int r)
+{
+    const float inv = 1.0f / (float)r;
+    for (int64_t m = (int64_t)blockIdx.x * kBlock + threadIdx.x; m < n_out; m += (int64_t)gridDim.x * kBlock) {
+        const float g = load_elem<BF16>(dy, m) * inv;
+        for (int j = 0; j < r; ++j) store_elem<BF16>(dx, m * r + j, g);
+    }
+}
+
 }  // namespace s2a

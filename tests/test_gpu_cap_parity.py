@@ -1,0 +1,73 @@
+"""GPU parity of Channel Average Pooling (s2a_cap_fwd / s2a_cap_bwd) against the
+oracle.  y is a short fp32 sum: |err| <= 1e-6 * mean_j |x_j| of its group (+ 1
+bf16 ulp of y for bf16 storage).  dx = dy / r is a power-of-two scaling: exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_08154_amd import s2a
+from paper_2503_08154_amd import workloads as wl
+
+import gpu_util as gu
+import parity
+
+pytestmark = pytest.mark.gpu
+DTYPES = [wl.F32, wl.BF16]
+
+
+def _run(x, dy, r, dtype, offset=0):
+    n_in, n_out = x.shape[0], dy.shape[0]
+    es = gu.esize(dtype)
+    st = torch.cuda.current_stream().cuda_stream
+    bx = gu.Buf(n_in * es, offset * es).upload(x)
+    by = gu.Buf(n_out * es, offset * es, fill=0xFF)
+    s2a.cap_fwd(bx.ptr, by.ptr, n_out, r, dtype, st)
+    bdy = gu.Buf(n_out * es, offset * es).upload(dy)
+    bdx = gu.Buf(n_in * es, offset * es, fill=0xFF)
+    s2a.cap_bwd(bdy.ptr, bdx.ptr, n_out, r, dtype, st)
+    torch.cuda.synchronize()
+    assert bx.canaries_intact() and by.canaries_intact() and bdy.canaries_intact() and bdx.canaries_intact()
+    return by.download(gu.storage_np(dtype)), bdx.download(gu.storage_np(dtype))
+
+
+def _check(n_out, r, dtype, seed, offset=0):
+    x = wl.draw_x(n_out * r, "student_t", 2.0, dtype, seed=seed)
+    dy = wl.draw_dy(n_out, 1.0, dtype, seed=seed + 1)
+    y, dx = _run(x, dy, r, dtype, offset)
+    y_ref = oracle.cap_fwd(x, dtype, r)
+    tol = 1e-6 * np.abs(wl.storage_to_f64(x, dtype)).reshape(n_out, r).mean(axis=1) if n_out else np.empty(0)
+    if dtype == wl.BF16:
+        tol = tol + parity.bf16_ulp(y_ref)
+    err = np.abs(wl.storage_to_f64(y, dtype) - y_ref)
+    assert (err <= tol).all(), f"y: worst {np.max(err / np.maximum(tol, 1e-300)):.2f}x the tolerance"
+    np.testing.assert_array_equal(wl.storage_to_f64(dx, dtype), oracle.cap_bwd(dy, dtype, r))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r", [2, 4, 8, 16, 32, 64])
+@pytest.mark.parametrize("n_out", [0, 1, 2, 3, 5, 31, 63, 64, 65, 257, 1023, 4097, 64 * 197 * 96 // 64])
+def test_sizes(dtype, r, n_out):
+    _check(n_out, r, dtype, seed=10 * r + n_out)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r", [2, 8, 32])
+def test_unaligned(dtype, r):
+    _check(4099, r, dtype, seed=77, offset=1)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_vit_b16_tokens_full_size(dtype):
+    """[64, 197, 768] backbone features pooled 8x to [64, 197, 96] (the paper's setting)."""
+    _check(64 * 197 * 96, 8, dtype, seed=5)
+
+
+def test_argument_errors():
+    fake = 0x1000
+    for bad_r in (0, 1, 3, 6, 128, -8):
+        assert s2a.cap_fwd(fake, fake, 8, bad_r, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.cap_fwd(fake, fake, -1, 8, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.cap_bwd(fake, fake, 8, 8, 5, check=False) == s2a.ERR_DTYPE
+    assert s2a.cap_bwd(None, fake, 8, 8, s2a.BF16, check=False) == s2a.ERR_NULL
+    assert s2a.cap_fwd(None, None, 0, 8, s2a.BF16, check=False) == s2a.OK
