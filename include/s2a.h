@@ -47,7 +47,7 @@ enum {
     S2A_ERR_LEVELS = -4,   /* s2a_qtable_init: levels != 16 */
     S2A_ERR_NOT_INIT = -5, /* s2a_qtable_init has not succeeded yet */
     S2A_ERR_LAUNCH = -6,   /* the HIP runtime refused the launch */
-    S2A_ERR_ALIGN = -7     /* qstate / qparams is not 4-byte aligned */
+    S2A_ERR_ALIGN = -7     /* a buffer lacks the alignment its entry point requires */
 };
 
 /* Floats of device memory behind a `qstate` pointer (see s2a_act_fwd_dyn). */
@@ -200,6 +200,26 @@ int s2a_softmax_bwd(const void* dy, const uint8_t* codes, const float* qparams, 
  */
 int s2a_cap_fwd(const void* x, void* y, int64_t n_out, int r, int dtype, void* stream);
 int s2a_cap_bwd(const void* dy, void* dx, int64_t n_out, int r, int dtype, void* stream);
+
+/*
+ * Low-Rank Prompt (Sec. 3.1, "Low-Rank Prompt (LRP)" paragraph, Eq. 3-4):
+ *   forward   y[b] = x[b] + A B            for every sample b of the batch
+ *   backward  dL/dx = dL/dy (alias it; nothing to compute),
+ *             dA = sum_b dL/dy[b] B^T,  dB = sum_b A^T dL/dy[b]
+ * Neither x nor y is needed in backward.
+ *   x, y, dy  device, batch*N*C elements of `dtype` (sample-major, then token,
+ *             then channel), 16-byte aligned (else S2A_ERR_ALIGN); y may equal x
+ *   A, dA     device, fp32 [N x r] row-major;  B, dB  device, fp32 [r x C]
+ *   work      device, N*C floats of scratch owned by the caller (holds the
+ *             batch-summed gradient between the kernels of one call)
+ *   r         1..64 (the paper uses 30); C a multiple of 8 (bf16) or 4 (fp32),
+ *             else S2A_ERR_SIZE
+ * Forward is one kernel; backward enqueues three.  Needs no s2a_qtable_init.
+ */
+int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t batch, int64_t N,
+                int64_t C, int r, int dtype, void* stream);
+int s2a_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float* dB, float* work,
+                int64_t batch, int64_t N, int64_t C, int r, int dtype, void* stream);
 
 /* Static, NUL-terminated description of a return code.  Never NULL. */
 const char* s2a_strerror(int code);

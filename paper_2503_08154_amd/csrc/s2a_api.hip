@@ -364,6 +364,17 @@ int check_cap(const void* a, const void* b, int64_t n_out, int r, int dtype)
     return S2A_OK;
 }
 
+int check_lrp(int64_t batch, int64_t N, int64_t C, int r, int dtype)
+{
+    if (dtype != S2A_F32 && dtype != S2A_BF16) return S2A_ERR_DTYPE;
+    const int epv = dtype == S2A_BF16 ? 8 : 4;
+    if (batch < 0 || N < 0 || C < 0 || r < 1 || r > s2a::kLrpMaxRank) return S2A_ERR_SIZE;
+    if (C % epv != 0) return S2A_ERR_SIZE;                       // a row of channels is whole 16-byte vectors
+    if (batch > 0x7fffffff || N > 0x7fffffff || C > 0x7fffffff) return S2A_ERR_SIZE;
+    if (N * C > 0x7fffffffLL * epv) return S2A_ERR_SIZE;         // vectors per sample fit an int
+    return S2A_OK;
+}
+
 static_assert(s2a::kQsFloats == S2A_QSTATE_FLOATS, "header and kernels disagree on the qstate size");
 
 }  // namespace
@@ -509,6 +520,66 @@ int s2a_cap_bwd(const void* dy, void* dx, int64_t n_out, int r, int dtype, void*
                              : launch_cap<false>(false, dy, dx, dx, n_out, r, st);
 }
 
+int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t batch, int64_t N,
+                int64_t C, int r, int dtype, void* stream)
+{
+    int rc = check_lrp(batch, N, C, r, dtype);
+    if (rc != S2A_OK) return rc;
+    if (batch == 0 || N == 0 || C == 0) return S2A_OK;
+    if (!x || !y || !A || !B) return S2A_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(A, 4) || !aligned(B, 4)) return S2A_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    // enough blocks to fill the chip: N tokens x batch chunks of at least 4 samples
+    int chunks = (int)((2048 + N - 1) / N);
+    if (chunks > (batch + 3) / 4) chunks = (int)((batch + 3) / 4);
+    if (chunks < 1) chunks = 1;
+    if (chunks > 65535) chunks = 65535;
+    const int per = (int)((batch + chunks - 1) / chunks);
+    chunks = (int)((batch + per - 1) / per);
+    dim3 grid((unsigned)N, (unsigned)chunks);
+    return checked_launch([&] {
+        if (dtype == S2A_BF16)
+            s2a::lrp_fwd_kernel<true><<<grid, dim3(s2a::kLrpBlock), 0, st>>>(
+                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r, per);
+        else
+            s2a::lrp_fwd_kernel<false><<<grid, dim3(s2a::kLrpBlock), 0, st>>>(
+                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r, per);
+    });
+}
+
+int s2a_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float* dB, float* work,
+                int64_t batch, int64_t N, int64_t C, int r, int dtype, void* stream)
+{
+    int rc = check_lrp(batch, N, C, r, dtype);
+    if (rc != S2A_OK) return rc;
+    if (N == 0 || C == 0) return S2A_OK;
+    if ((batch > 0 && !dy) || !A || !B || !dA || !dB || !work) return S2A_ERR_NULL;
+    if (!aligned(dy, 16) || !aligned(A, 4) || !aligned(B, 4) || !aligned(dA, 4) || !aligned(dB, 4) || !aligned(work, 4))
+        return S2A_ERR_ALIGN;
+    if ((C + s2a::kLrpBlock - 1) / s2a::kLrpBlock > 65535 || N > 0x7fffffff) return S2A_ERR_SIZE;
+    hipStream_t st = (hipStream_t)stream;
+    const int epv = dtype == S2A_BF16 ? 8 : 4;
+    const int64_t sample_vecs = N * C / epv;
+    const int64_t blocks = (sample_vecs + s2a::kLrpBlock - 1) / s2a::kLrpBlock;
+    rc = checked_launch([&] {
+        if (dtype == S2A_BF16)
+            s2a::lrp_batch_sum_kernel<true><<<dim3((unsigned)blocks), dim3(s2a::kLrpBlock), 0, st>>>(
+                (const s2a::u32x4*)dy, work, (int)batch, sample_vecs);
+        else
+            s2a::lrp_batch_sum_kernel<false><<<dim3((unsigned)blocks), dim3(s2a::kLrpBlock), 0, st>>>(
+                (const s2a::u32x4*)dy, work, (int)batch, sample_vecs);
+    });
+    if (rc != S2A_OK) return rc;
+    rc = checked_launch([&] {
+        s2a::lrp_grad_a_kernel<<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
+    });
+    if (rc != S2A_OK) return rc;
+    return checked_launch([&] {
+        s2a::lrp_grad_b_kernel<<<dim3((unsigned)((C + s2a::kLrpBlock - 1) / s2a::kLrpBlock), (unsigned)r),
+                                 dim3(s2a::kLrpBlock), 0, st>>>(work, A, dB, (int)N, (int)C, r);
+    });
+}
+
 const char* s2a_strerror(int code)
 {
     switch (code) {
@@ -519,7 +590,7 @@ const char* s2a_strerror(int code)
         case S2A_ERR_LEVELS: return "only 16 quantization levels (4-bit codes) are supported";
         case S2A_ERR_NOT_INIT: return "s2a_qtable_init has not been called";
         case S2A_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
-        case S2A_ERR_ALIGN: return "qstate / qparams is not 4-byte aligned";
+        case S2A_ERR_ALIGN: return "a buffer does not have the alignment its entry point requires";
         default: return "unknown s2a error code";
     }
 }

@@ -1271,4 +1271,139 @@ __global__ __launch_bounds__(kBlock) void cap_bwd_kernel_unaligned(const void* d
     }
 }
 
+// ------------------------------------------------ Low-Rank Prompt ----------
+//
+// Sec. 3.1, "Low-Rank Prompt (LRP)" paragraph, Eq. 3-4: y = x + A B with
+// A [N x r], B [r x C] (fp32 parameters), the same prompt for every sample of
+// the batch; dL/dx = dL/dy, dL/dA = dL/dy B^T, dL/dB = A^T dL/dy, both summed
+// over the batch.  Neither x nor y is needed in backward.
+//
+// Forward: the prompt is never materialised.  A block owns one token i and a
+// chunk of the batch; each lane owns 16-byte vectors of channels, forms its
+// EPV prompt values P[i, c..] = sum_k A[i,k] B[k,c..] once (A[i,:] is uniform
+// over the block, B comes from L2) and then streams x -> y over its batch
+// chunk with four loads in flight.  HBM traffic: x once, y once.
+// Backward: G = sum_b dL/dy[b] is formed once (a streaming pass over dL/dy,
+// fp32, into a caller-provided N*C workspace), then dA = G B^T (one block per
+// token) and dB = A^T G (one lane per (k, c)); the two products are tiny
+// (N*C*r = 4.5 MFLOP at ViT-B/16) next to the pass over dL/dy.
+constexpr int kLrpBlock = 256;
+constexpr int kLrpMaxRank = 64;
+
+template <bool BF16>
+__global__ __launch_bounds__(kLrpBlock) void lrp_fwd_kernel(const u32x4* x, u32x4* y,
+                                                            const float* __restrict__ A,
+                                                            const float* __restrict__ B,
+                                                            int batch, int N, int C, int r,
+                                                            int batch_chunk)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    const int i = blockIdx.x;  // token
+    const int b0 = blockIdx.y * batch_chunk;
+    const int b1 = b0 + batch_chunk < batch ? b0 + batch_chunk : batch;
+    const int cvecs = C / EPV;  // C is a multiple of EPV (the launcher checks)
+    const float* Ai = A + (int64_t)i * r;
+    for (int cv = threadIdx.x; cv < cvecs; cv += kLrpBlock) {
+        float p[EPV];
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) p[j] = 0.0f;
+        for (int k = 0; k < r; ++k) {
+            const float a = Ai[k];
+            const float* Bk = B + (int64_t)k * C + cv * EPV;
+#pragma unroll
+            for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a, Bk[j], p[j]);
+        }
+        const int64_t sample = (int64_t)N * cvecs;          // vectors per sample
+        const int64_t at = (int64_t)i * cvecs + cv;          // this lane's vector inside a sample
+        constexpr int U = 4;
+        for (int b = b0; b < b1; b += U) {
+            u32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (b + u < b1) v[u] = stream_load128(x + (b + u) * sample + at);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (b + u < b1) {
+                    float f[EPV];
+                    unpack_vector<BF16>(v[u], f);
+                    u32x4 o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        o[j] = BF16 ? pack_bf16(f[2 * j] + p[2 * j], f[2 * j + 1] + p[2 * j + 1]) : as_u32(f[j] + p[j]);
+                    stream_store128(y + (b + u) * sample + at, o);
+                }
+        }
+    }
+}
+
+// G[i, c] = sum_b dy[b, i, c], fp32.  One lane per 16-byte vector of a sample.
+template <bool BF16>
+__global__ __launch_bounds__(kLrpBlock) void lrp_batch_sum_kernel(const u32x4* dy,
+                                                                  float* __restrict__ G, int batch,
+                                                                  int64_t sample_vecs)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    const int64_t at = (int64_t)blockIdx.x * kLrpBlock + threadIdx.x;
+    if (at >= sample_vecs) return;
+    float acc[EPV];
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) acc[j] = 0.0f;
+    constexpr int U = 8;
+    for (int b = 0; b < batch; b += U) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (b + u < batch) v[u] = stream_load128(dy + (b + u) * sample_vecs + at);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (b + u < batch) {
+                float f[EPV];
+                unpack_vector<BF16>(v[u], f);
+#pragma unroll
+                for (int j = 0; j < EPV; ++j) acc[j] += f[j];
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) G[at * EPV + j] = acc[j];
+}
+
+// dA[i, k] = sum_c G[i, c] B[k, c].  One block per token; lanes stride over c,
+// then the r partial sums are reduced over the block.
+__global__ __launch_bounds__(kLrpBlock) void lrp_grad_a_kernel(const float* __restrict__ G,
+                                                               const float* __restrict__ B,
+                                                               float* __restrict__ dA, int C, int r)
+{
+    __shared__ float part[kLrpBlock / kWave][kLrpMaxRank];
+    const int i = blockIdx.x;
+    const float* Gi = G + (int64_t)i * C;
+    for (int k = 0; k < r; ++k) {
+        float acc = 0.0f;
+        for (int c = threadIdx.x; c < C; c += kLrpBlock) acc = __builtin_fmaf(Gi[c], B[(int64_t)k * C + c], acc);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+        if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave][k] = acc;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < r) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kLrpBlock / kWave; ++w) acc += part[w][threadIdx.x];
+        dA[(int64_t)i * r + threadIdx.x] = acc;
+    }
+}
+
+// dB[k, c] = sum_i A[i, k] G[i, c].  blockIdx.y = k, one lane per c.
+__global__ __launch_bounds__(kLrpBlock) void lrp_grad_b_kernel(const float* __restrict__ G,
+                                                               const float* __restrict__ A,
+                                                               float* __restrict__ dB, int N, int C,
+                                                               int r)
+{
+    const int c = blockIdx.x * kLrpBlock + threadIdx.x;
+    const int k = blockIdx.y;
+    if (c >= C) return;
+    float acc = 0.0f;
+    for (int i = 0; i < N; ++i) acc = __builtin_fmaf(A[(int64_t)i * r + k], G[(int64_t)i * C + c], acc);
+    dB[(int64_t)k * C + c] = acc;
+}
+
 }  // namespace s2a
