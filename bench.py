@@ -187,6 +187,54 @@ def time_softmax(torch, rows: int, L: int, dtype: int, sets: int, steps: int, wa
     }
 
 
+def time_cap_lrp(torch, steps: int, warmup: int):
+    """Channel Average Pooling (r = 8) and Low-Rank Prompt (rank 30) on ViT-B/16 tokens [64, 197, 768] bf16,
+    16 distinct buffer sets each (the tensors are only 19 MB)."""
+    batch, N, C, r_cap, rank, sets = 64, 197, 768, 8, 30, 16
+    n = batch * N * C
+    x = wl.draw_x(n, "normal", 1.5, wl.BF16, 31)
+    dy = wl.draw_dy(n, 1e-2, wl.BF16, 32)
+    g = np.random.Generator(np.random.Philox(33))
+    A = torch.from_numpy((g.standard_normal((N, rank)) * 0.1).astype(np.float32)).cuda()
+    B = torch.from_numpy((g.standard_normal((rank, C)) * 0.1).astype(np.float32)).cuda()
+    bufs = []
+    for _ in range(sets):
+        tx = torch.from_numpy(x.view(np.uint8)).cuda()
+        tdy = torch.from_numpy(dy.view(np.uint8)).cuda()
+        bufs.append(dict(x=tx, y=torch.empty_like(tx), dy=tdy, dx=torch.empty_like(tdy),
+                         pooled=torch.empty(n // r_cap * 2, dtype=torch.uint8, device="cuda"),
+                         dpooled=tdy[: n // r_cap * 2].clone(),
+                         dA=torch.empty(N, rank, device="cuda"), dB=torch.empty(rank, C, device="cuda"),
+                         work=torch.empty(N, C, device="cuda")))
+    st = torch.cuda.current_stream().cuda_stream
+    ops = {
+        "cap_fwd": lambda b: s2a.cap_fwd(b["x"].data_ptr(), b["pooled"].data_ptr(), n // r_cap, r_cap, wl.BF16, st),
+        "cap_bwd": lambda b: s2a.cap_bwd(b["dpooled"].data_ptr(), b["dx"].data_ptr(), n // r_cap, r_cap, wl.BF16, st),
+        "lrp_fwd": lambda b: s2a.lrp_fwd(b["x"].data_ptr(), b["y"].data_ptr(), A.data_ptr(), B.data_ptr(), batch, N, C, rank, wl.BF16, st),
+        "lrp_bwd": lambda b: s2a.lrp_bwd(b["dy"].data_ptr(), A.data_ptr(), B.data_ptr(), b["dA"].data_ptr(), b["dB"].data_ptr(),
+                                         b["work"].data_ptr(), batch, N, C, rank, wl.BF16, st),
+    }
+    nbytes = {"cap_fwd": 2 * n + 2 * n // r_cap, "cap_bwd": 2 * n + 2 * n // r_cap, "lrp_fwd": 4 * n,
+              "lrp_bwd": 2 * n + 4 * (2 * N * C + 2 * (N * rank + rank * C))}
+    out = {"shape": "[64, 197, 768] bf16, CAP r=8, LRP rank 30", "buffer_sets": sets}
+    for name, fn in ops.items():
+        for _ in range(warmup):
+            for b in bufs:
+                fn(b)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            for b in bufs:
+                fn(b)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (steps * sets)
+        out[name] = {"us": round(us, 2), "gbs": round(nbytes[name] / us / 1e3, 1),
+                     "frac": round(nbytes[name] / us / 1e3 / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_launch": nbytes[name]}
+    return out
+
+
 def roofline_of(res, w: wl.Workload):
     """Roofline entry of the slower of the two kernels."""
     which = "fwd" if res["fwd_us_per_launch"] >= res["bwd_us_per_launch"] else "bwd"
@@ -348,6 +396,8 @@ def main():
             "vit_b16_attention_bf16": time_softmax(torch, 64 * 12 * 197, 197, wl.BF16, 12, max(5, args.steps // 2), 5),
             "vit_b16_attention_f32": time_softmax(torch, 64 * 12 * 197, 197, wl.F32, 8, max(5, args.steps // 2), 5),
         }
+        # next row: the activation-free parametric modules either side of the nonlinearity
+        out["cap_lrp"] = time_cap_lrp(torch, max(5, args.steps // 2), 5)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -529,9 +529,10 @@ int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t 
     if (!x || !y || !A || !B) return S2A_ERR_NULL;
     if (!aligned(x, 16) || !aligned(y, 16) || !aligned(A, 4) || !aligned(B, 4)) return S2A_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    // enough blocks to fill the chip: N tokens x batch chunks of at least 4 samples
-    int chunks = (int)((2048 + N - 1) / N);
-    if (chunks > (batch + 3) / 4) chunks = (int)((batch + 3) / 4);
+    // about 800 blocks fill the chip; a block re-reads B (r*C floats, from L2) once per batch chunk,
+    // so chunks are kept at 8 samples or more
+    int chunks = (int)((800 + N - 1) / N);
+    if (chunks > (batch + 7) / 8) chunks = (int)((batch + 7) / 8);
     if (chunks < 1) chunks = 1;
     if (chunks > 65535) chunks = 65535;
     const int per = (int)((batch + chunks - 1) / chunks);
@@ -556,26 +557,29 @@ int s2a_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float
     if ((batch > 0 && !dy) || !A || !B || !dA || !dB || !work) return S2A_ERR_NULL;
     if (!aligned(dy, 16) || !aligned(A, 4) || !aligned(B, 4) || !aligned(dA, 4) || !aligned(dB, 4) || !aligned(work, 4))
         return S2A_ERR_ALIGN;
-    if ((C + s2a::kLrpBlock - 1) / s2a::kLrpBlock > 65535 || N > 0x7fffffff) return S2A_ERR_SIZE;
+    if (N > 0x7fffffff) return S2A_ERR_SIZE;
     hipStream_t st = (hipStream_t)stream;
-    const int epv = dtype == S2A_BF16 ? 8 : 4;
-    const int64_t sample_vecs = N * C / epv;
-    const int64_t blocks = (sample_vecs + s2a::kLrpBlock - 1) / s2a::kLrpBlock;
+    const int64_t sample_words = dtype == S2A_BF16 ? N * C / 2 : N * C;
+    const int64_t blocks = (sample_words + s2a::kLrpBlock - 1) / s2a::kLrpBlock;
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     rc = checked_launch([&] {
         if (dtype == S2A_BF16)
             s2a::lrp_batch_sum_kernel<true><<<dim3((unsigned)blocks), dim3(s2a::kLrpBlock), 0, st>>>(
-                (const s2a::u32x4*)dy, work, (int)batch, sample_vecs);
+                (const uint32_t*)dy, work, (int)batch, sample_words);
         else
             s2a::lrp_batch_sum_kernel<false><<<dim3((unsigned)blocks), dim3(s2a::kLrpBlock), 0, st>>>(
-                (const s2a::u32x4*)dy, work, (int)batch, sample_vecs);
+                (const uint32_t*)dy, work, (int)batch, sample_words);
     });
     if (rc != S2A_OK) return rc;
     rc = checked_launch([&] {
-        s2a::lrp_grad_a_kernel<<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
+        if (r <= 8) s2a::lrp_grad_a_kernel<8><<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
+        else if (r <= 16) s2a::lrp_grad_a_kernel<16><<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
+        else if (r <= 32) s2a::lrp_grad_a_kernel<32><<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
+        else s2a::lrp_grad_a_kernel<64><<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
     });
     if (rc != S2A_OK) return rc;
     return checked_launch([&] {
-        s2a::lrp_grad_b_kernel<<<dim3((unsigned)((C + s2a::kLrpBlock - 1) / s2a::kLrpBlock), (unsigned)r),
+        s2a::lrp_grad_b_kernel<<<dim3((unsigned)((C + s2a::kWave - 1) / s2a::kWave), (unsigned)r),
                                  dim3(s2a::kLrpBlock), 0, st>>>(work, A, dB, (int)N, (int)C, r);
     });
 }

@@ -1282,7 +1282,7 @@ __global__ __launch_bounds__(kBlock) void cap_bwd_kernel_unaligned(const void* d
 // chunk of the batch; each lane owns 16-byte vectors of channels, forms its
 // EPV prompt values P[i, c..] = sum_k A[i,k] B[k,c..] once (A[i,:] is uniform
 // over the block, B comes from L2) and then streams x -> y over its batch
-// chunk with four loads in flight.  HBM traffic: x once, y once.
+// chunk with eight loads in flight.  HBM traffic: x once, y once.
 // Backward: G = sum_b dL/dy[b] is formed once (a streaming pass over dL/dy,
 // fp32, into a caller-provided N*C workspace), then dA = G B^T (one block per
 // token) and dB = A^T G (one lane per (k, c)); the two products are tiny
@@ -1315,7 +1315,7 @@ __global__ __launch_bounds__(kLrpBlock) void lrp_fwd_kernel(const u32x4* x, u32x
         }
         const int64_t sample = (int64_t)N * cvecs;          // vectors per sample
         const int64_t at = (int64_t)i * cvecs + cv;          // this lane's vector inside a sample
-        constexpr int U = 4;
+        constexpr int U = 8;
         for (int b = b0; b < b1; b += U) {
             u32x4 v[U];
 #pragma unroll
@@ -1336,74 +1336,118 @@ __global__ __launch_bounds__(kLrpBlock) void lrp_fwd_kernel(const u32x4* x, u32x
     }
 }
 
-// G[i, c] = sum_b dy[b, i, c], fp32.  One lane per 16-byte vector of a sample.
+// G[i, c] = sum_b dy[b, i, c], fp32.  One lane per dword of a sample (two bf16
+// or one fp32): a sample is only ~150 k elements, so narrow lanes are what
+// fills the chip; eight loads per lane are in flight.
 template <bool BF16>
-__global__ __launch_bounds__(kLrpBlock) void lrp_batch_sum_kernel(const u32x4* dy,
+__global__ __launch_bounds__(kLrpBlock) void lrp_batch_sum_kernel(const uint32_t* dy,
                                                                   float* __restrict__ G, int batch,
-                                                                  int64_t sample_vecs)
+                                                                  int64_t sample_words)
 {
-    constexpr int EPV = BF16 ? 8 : 4;
     const int64_t at = (int64_t)blockIdx.x * kLrpBlock + threadIdx.x;
-    if (at >= sample_vecs) return;
-    float acc[EPV];
-#pragma unroll
-    for (int j = 0; j < EPV; ++j) acc[j] = 0.0f;
+    if (at >= sample_words) return;
+    float acc0 = 0.0f, acc1 = 0.0f;
     constexpr int U = 8;
     for (int b = 0; b < batch; b += U) {
-        u32x4 v[U];
+        uint32_t w[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (b + u < batch) v[u] = stream_load128(dy + (b + u) * sample_vecs + at);
+            if (b + u < batch) w[u] = stream_load32(dy + (b + u) * sample_words + at);
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (b + u < batch) {
-                float f[EPV];
-                unpack_vector<BF16>(v[u], f);
-#pragma unroll
-                for (int j = 0; j < EPV; ++j) acc[j] += f[j];
+                if (BF16) {
+                    acc0 += bf16_lo(w[u]);
+                    acc1 += bf16_hi(w[u]);
+                } else {
+                    acc0 += as_f32(w[u]);
+                }
             }
     }
-#pragma unroll
-    for (int j = 0; j < EPV; ++j) G[at * EPV + j] = acc[j];
+    if (BF16) {
+        G[2 * at] = acc0;
+        G[2 * at + 1] = acc1;
+    } else {
+        G[at] = acc0;
+    }
 }
 
-// dA[i, k] = sum_c G[i, c] B[k, c].  One block per token; lanes stride over c,
-// then the r partial sums are reduced over the block.
+// dA[i, k] = sum_c G[i, c] B[k, c].  One block per token; every lane keeps all
+// the partial sums of its channels (RMAX >= r of them, independent chains), then
+// the sums are reduced over the wave by cross-lane moves and over the block
+// through LDS.
+template <int RMAX>
 __global__ __launch_bounds__(kLrpBlock) void lrp_grad_a_kernel(const float* __restrict__ G,
                                                                const float* __restrict__ B,
                                                                float* __restrict__ dA, int C, int r)
 {
-    __shared__ float part[kLrpBlock / kWave][kLrpMaxRank];
+    __shared__ float part[kLrpBlock / kWave][RMAX];
     const int i = blockIdx.x;
     const float* Gi = G + (int64_t)i * C;
-    for (int k = 0; k < r; ++k) {
-        float acc = 0.0f;
-        for (int c = threadIdx.x; c < C; c += kLrpBlock) acc = __builtin_fmaf(Gi[c], B[(int64_t)k * C + c], acc);
+    float acc[RMAX];
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-        if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave][k] = acc;
+    for (int k = 0; k < RMAX; ++k) acc[k] = 0.0f;
+    for (int c = threadIdx.x; c < C; c += kLrpBlock) {
+        const float g = Gi[c];
+#pragma unroll
+        for (int k = 0; k < RMAX; ++k)
+            if (k < r) acc[k] = __builtin_fmaf(g, B[(int64_t)k * C + c], acc[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < RMAX; ++k) {
+        float v = acc[k];
+        v += dpp_move<kDppXor1>(v);
+        v += dpp_move<kDppXor2>(v);
+        v += dpp_move<kDppHalfMirror>(v);
+        v += dpp_move<kDppMirror>(v);
+        v += __shfl_xor(v, 16, kWave);
+        v += __shfl_xor(v, 32, kWave);
+        acc[k] = v;
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+#pragma unroll
+        for (int k = 0; k < RMAX; ++k) part[threadIdx.x / kWave][k] = acc[k];
     }
     __syncthreads();
     if ((int)threadIdx.x < r) {
-        float acc = 0.0f;
+        float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kLrpBlock / kWave; ++w) acc += part[w][threadIdx.x];
-        dA[(int64_t)i * r + threadIdx.x] = acc;
+        for (int w = 0; w < kLrpBlock / kWave; ++w) v += part[w][threadIdx.x];
+        dA[(int64_t)i * r + threadIdx.x] = v;
     }
 }
 
-// dB[k, c] = sum_i A[i, k] G[i, c].  blockIdx.y = k, one lane per c.
+// dB[k, c] = sum_i A[i, k] G[i, c].  blockIdx.y = k; a block covers 64 channels,
+// its four waves split the tokens and add up through LDS.
 __global__ __launch_bounds__(kLrpBlock) void lrp_grad_b_kernel(const float* __restrict__ G,
                                                                const float* __restrict__ A,
                                                                float* __restrict__ dB, int N, int C,
                                                                int r)
 {
-    const int c = blockIdx.x * kLrpBlock + threadIdx.x;
+    __shared__ float part[kLrpBlock / kWave][kWave];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int c = blockIdx.x * kWave + lane;
     const int k = blockIdx.y;
-    if (c >= C) return;
-    float acc = 0.0f;
-    for (int i = 0; i < N; ++i) acc = __builtin_fmaf(A[(int64_t)i * r + k], G[(int64_t)i * C + c], acc);
-    dB[(int64_t)k * C + c] = acc;
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;  // independent chains
+    if (c < C) {
+        constexpr int W = kLrpBlock / kWave;
+        int i = wave;
+        for (; i + 3 * W < N; i += 4 * W) {
+            a0 = __builtin_fmaf(A[(int64_t)i * r + k], G[(int64_t)i * C + c], a0);
+            a1 = __builtin_fmaf(A[(int64_t)(i + W) * r + k], G[(int64_t)(i + W) * C + c], a1);
+            a2 = __builtin_fmaf(A[(int64_t)(i + 2 * W) * r + k], G[(int64_t)(i + 2 * W) * C + c], a2);
+            a3 = __builtin_fmaf(A[(int64_t)(i + 3 * W) * r + k], G[(int64_t)(i + 3 * W) * C + c], a3);
+        }
+        for (; i < N; i += W) a0 = __builtin_fmaf(A[(int64_t)i * r + k], G[(int64_t)i * C + c], a0);
+    }
+    part[wave][lane] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (wave == 0 && c < C) {
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kLrpBlock / kWave; ++w) v += part[w][lane];
+        dB[(int64_t)k * C + c] = v;
+    }
 }
 
 }  // namespace s2a
