@@ -192,97 +192,124 @@ int softmax_group(int64_t L)
     return 0;
 }
 
-// LDS bytes of one softmax block: the data span (+ up to 15 bytes of lead-in and
-// padding to a vector), then the codes span.
-// Row groups per block of the staged kernels, by measurement at the ViT-B/16
-// attention shape: the bf16 backward kernel gains 10 % from twice the bytes in
-// flight per block; the others lose from the lower block count and occupancy.
-constexpr int kFwdPasses = 1;
+// The staged kernels (16-byte aligned buffers) give each lane element pairs:
+// G lanes per row, the smallest of 4 .. 64 whose lanes hold at most
+// pair_slots() pairs each, and exactly ceil(pairs / G) slots compiled in.
+// Slot limit by measurement at the ViT-B/16 attention shape (197-long rows):
+// bf16 runs fastest with 8 lanes x 13 pairs, fp32 with 16 lanes x 7 pairs.
 template <bool BF16>
-constexpr int bwd_passes() { return BF16 ? 2 : 1; }
+constexpr int pair_slots() { return BF16 ? 16 : 8; }
+template <bool BF16>
+int softmax_pair_group(int64_t L)
+{
+    const int64_t pairs = (L + 1) / 2;
+    for (int g = 4; g <= 64; g *= 2)
+        if ((pairs + g - 1) / g <= pair_slots<BF16>()) return g;
+    return 0;
+}
+
+// Row groups per block of the staged kernels, by measurement at the ViT-B/16
+// attention shape.
+template <bool BF16>
+constexpr int fwd_passes() { return 1; }
+template <bool BF16>
+constexpr int bwd_passes() { return 1; }
+
+// LDS bytes of one staged softmax block: the data span (+ up to 15 bytes of
+// lead-in and padding to a vector), then the codes span.
+// Lanes per block of the staged kernels: 256 measured fastest of 64 .. 1024.
+constexpr int kStagedBlock = 256;
+template <bool BF16, int G>
+void softmax_lds(int L, int passes, int* data_bytes, int* total_bytes)
+{
+    const int rpb = passes * kStagedBlock / G, es = BF16 ? 2 : 4;
+    *data_bytes = ((rpb * L * es + 15 + 15) / 16) * 16;
+    *total_bytes = *data_bytes + ((rpb * ((L + 1) / 2) + 15 + 15) / 16) * 16;
+}
+
+// Calls f(std::integral_constant<int, SLOTS>) for SLOTS == slots.  Groups wider
+// than 4 lanes only occur for rows that need more than half the slots.
+template <int G, int MAXS, int S = MAXS, typename F>
+void with_slots(int slots, F f)
+{
+    if (slots == S) f(std::integral_constant<int, S>{});
+    else if constexpr (S > (G == 4 ? 1 : MAXS / 2 + 1)) with_slots<G, MAXS, S - 1>(slots, f);
+}
 
 template <bool BF16, int G>
-void softmax_lds(int L, int passes, int* data_bytes, int* codes_bytes, int* total_bytes)
+int launch_softmax_fwd_staged(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
+                              hipStream_t st)
 {
-    const int rpb = passes * s2a::kSoftmaxBlock / G, es = BF16 ? 2 : 4;
-    *data_bytes = ((rpb * L * es + 15 + 15) / 16) * 16;
-    *codes_bytes = ((rpb * ((L + 1) / 2) + 15 + 15) / 16) * 16;
-    *total_bytes = *data_bytes + *codes_bytes + 16;  // + the spare slot dead lanes write to
+    constexpr int P = fwd_passes<BF16>();
+    const int rpb = P * kStagedBlock / G;
+    const int64_t blocks = (rows + rpb - 1) / rpb;
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    int data_bytes, total;
+    softmax_lds<BF16, G>(L, P, &data_bytes, &total);
+    return checked_launch([&] {
+        with_slots<G, pair_slots<BF16>()>(((L + 1) / 2 + G - 1) / G, [&](auto sc) {
+            s2a::softmax_fwd_staged<BF16, G, P, decltype(sc)::value, kStagedBlock>
+                <<<dim3((unsigned)blocks), dim3(kStagedBlock), total, st>>>(x, y, codes, qp, rows, L, data_bytes);
+        });
+    });
 }
-
-// Slot buckets of the staged kernels (13 = 197-long rows with 16 lanes, 7 = 49 with 8, 9 = 257 with 32).
-template <bool BF16, int G, int SLOTS>
-void softmax_fwd_staged_launch(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
-                               unsigned blocks, int total, int data_bytes, int codes_bytes, hipStream_t st)
+template <bool BF16, int G>
+int launch_softmax_bwd_staged(const void* dy, const uint8_t* codes, const float* qp, void* dx,
+                              int64_t rows, int L, hipStream_t st)
 {
-    s2a::softmax_fwd_staged<BF16, G, kFwdPasses, SLOTS><<<dim3(blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
-        x, y, codes, qp, rows, L, data_bytes, codes_bytes);
-}
-template <bool BF16, int G, int SLOTS>
-void softmax_bwd_staged_launch(const void* dy, const uint8_t* codes, const float* qp, void* dx, int64_t rows,
-                               int L, unsigned blocks, int total, int data_bytes, int codes_bytes, hipStream_t st)
-{
-    s2a::softmax_bwd_staged<BF16, G, bwd_passes<BF16>(), SLOTS><<<dim3(blocks), dim3(s2a::kSoftmaxBlock), total, st>>>(
-        dy, codes, qp, dx, rows, L, data_bytes, codes_bytes);
-}
-// Calls f.template operator()<SLOTS>() for the smallest bucket that holds `slots`.
-// Groups wider than 8 lanes only occur for rows that need at least 9 slots.
-template <int G, typename F>
-void with_slot_bucket(int slots, F f)
-{
-    if (G == 8 && slots <= 4) f(std::integral_constant<int, 4>{});
-    else if (G == 8 && slots <= 7) f(std::integral_constant<int, 7>{});
-    else if (slots <= 9) f(std::integral_constant<int, 9>{});
-    else if (slots <= 13) f(std::integral_constant<int, 13>{});
-    else f(std::integral_constant<int, 16>{});
+    constexpr int P = bwd_passes<BF16>();
+    const int rpb = P * kStagedBlock / G;
+    const int64_t blocks = (rows + rpb - 1) / rpb;
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    int data_bytes, total;
+    softmax_lds<BF16, G>(L, P, &data_bytes, &total);
+    return checked_launch([&] {
+        with_slots<G, pair_slots<BF16>()>(((L + 1) / 2 + G - 1) / G, [&](auto sc) {
+            s2a::softmax_bwd_staged<BF16, G, P, decltype(sc)::value, kStagedBlock>
+                <<<dim3((unsigned)blocks), dim3(kStagedBlock), total, st>>>(dy, codes, qp, dx, rows, L, data_bytes);
+        });
+    });
 }
 
 template <bool BF16, int G>
 int launch_softmax_fwd_g(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
                          hipStream_t st)
 {
-    const bool staged = aligned(x, 16) && aligned(y, 16) && aligned(codes, 16);
-    const int rpb = (staged ? kFwdPasses : 1) * s2a::kSoftmaxBlock / G;
-    int64_t blocks = (rows + rpb - 1) / rpb;
+    const int rpb = s2a::kSoftmaxBlock / G;
+    const int64_t blocks = (rows + rpb - 1) / rpb;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
-    int data_bytes, codes_bytes, total;
-    softmax_lds<BF16, G>(L, kFwdPasses, &data_bytes, &codes_bytes, &total);
     return checked_launch([&] {
-        if (staged)
-            with_slot_bucket<G>((L - 1) / G + 1, [&](auto sc) {
-                softmax_fwd_staged_launch<BF16, G, decltype(sc)::value>(x, y, codes, qp, rows, L, (unsigned)blocks,
-                                                                        total, data_bytes, codes_bytes, st);
-            });
-        else
-            s2a::softmax_fwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
-                x, y, codes, qp, rows, L);
+        s2a::softmax_fwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
+            x, y, codes, qp, rows, L);
     });
 }
 template <bool BF16, int G>
 int launch_softmax_bwd_g(const void* dy, const uint8_t* codes, const float* qp, void* dx,
                          int64_t rows, int L, hipStream_t st)
 {
-    const bool staged = aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 16);
-    const int rpb = (staged ? bwd_passes<BF16>() : 1) * s2a::kSoftmaxBlock / G;
-    int64_t blocks = (rows + rpb - 1) / rpb;
+    const int rpb = s2a::kSoftmaxBlock / G;
+    const int64_t blocks = (rows + rpb - 1) / rpb;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
-    int data_bytes, codes_bytes, total;
-    softmax_lds<BF16, G>(L, bwd_passes<BF16>(), &data_bytes, &codes_bytes, &total);
     return checked_launch([&] {
-        if (staged)
-            with_slot_bucket<G>((L - 1) / G + 1, [&](auto sc) {
-                softmax_bwd_staged_launch<BF16, G, decltype(sc)::value>(dy, codes, qp, dx, rows, L, (unsigned)blocks,
-                                                                        total, data_bytes, codes_bytes, st);
-            });
-        else
-            s2a::softmax_bwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
-                dy, codes, qp, dx, rows, L);
+        s2a::softmax_bwd_kernel<BF16, G><<<dim3((unsigned)blocks), dim3(s2a::kSoftmaxBlock), 0, st>>>(
+            dy, codes, qp, dx, rows, L);
     });
 }
 template <bool BF16>
 int launch_softmax_fwd(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
                        hipStream_t st)
 {
+    if (aligned(x, 16) && aligned(y, 16) && aligned(codes, 16))
+        switch (softmax_pair_group<BF16>(L)) {
+            case 4: return launch_softmax_fwd_staged<BF16, 4>(x, y, codes, qp, rows, L, st);
+            case 8: return launch_softmax_fwd_staged<BF16, 8>(x, y, codes, qp, rows, L, st);
+            case 16: return launch_softmax_fwd_staged<BF16, 16>(x, y, codes, qp, rows, L, st);
+            case 32: return launch_softmax_fwd_staged<BF16, 32>(x, y, codes, qp, rows, L, st);
+            case 64:  // only rows of fp32 reach 64 lanes
+                if constexpr (!BF16) return launch_softmax_fwd_staged<BF16, 64>(x, y, codes, qp, rows, L, st);
+                return S2A_ERR_SIZE;
+            default: return S2A_ERR_SIZE;
+        }
     switch (softmax_group(L)) {
         case 8: return launch_softmax_fwd_g<BF16, 8>(x, y, codes, qp, rows, L, st);
         case 16: return launch_softmax_fwd_g<BF16, 16>(x, y, codes, qp, rows, L, st);
@@ -295,6 +322,17 @@ template <bool BF16>
 int launch_softmax_bwd(const void* dy, const uint8_t* codes, const float* qp, void* dx,
                        int64_t rows, int L, hipStream_t st)
 {
+    if (aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 16))
+        switch (softmax_pair_group<BF16>(L)) {
+            case 4: return launch_softmax_bwd_staged<BF16, 4>(dy, codes, qp, dx, rows, L, st);
+            case 8: return launch_softmax_bwd_staged<BF16, 8>(dy, codes, qp, dx, rows, L, st);
+            case 16: return launch_softmax_bwd_staged<BF16, 16>(dy, codes, qp, dx, rows, L, st);
+            case 32: return launch_softmax_bwd_staged<BF16, 32>(dy, codes, qp, dx, rows, L, st);
+            case 64:  // only rows of fp32 reach 64 lanes
+                if constexpr (!BF16) return launch_softmax_bwd_staged<BF16, 64>(dy, codes, qp, dx, rows, L, st);
+                return S2A_ERR_SIZE;
+            default: return S2A_ERR_SIZE;
+        }
     switch (softmax_group(L)) {
         case 8: return launch_softmax_bwd_g<BF16, 8>(dy, codes, qp, dx, rows, L, st);
         case 16: return launch_softmax_bwd_g<BF16, 16>(dy, codes, qp, dx, rows, L, st);

@@ -670,12 +670,13 @@ __global__ __launch_bounds__(kBlock) void relu_bwd_kernel_unaligned(const void* 
 //   backward  yh = code*s + lo                                      (Eq. 9)
 //             dx_i = yh_i * (dy_i - sum_j yh_j dy_j)               (Eq. 7's Jacobian)
 //
-// A row is handled by a group of G lanes (G = 8, 16, 32 or 64, the smallest with
-// ceil(L/G) <= 16), so a wave holds 64/G rows and all row reductions are
-// cross-lane shuffles inside the group.  Lane l of the
-// group owns elements l, l+G, l+2G, ...; since G is even, elements 2j and 2j+1
-// sit in neighbouring lanes at the same step, and the even lane packs both
-// codes into the byte it stores.
+// A row is handled by a group of G lanes, so a wave holds 64/G rows and all
+// row reductions are cross-lane moves inside the group.  The kernels for
+// 16-byte aligned buffers give each lane element pairs (G = 4 .. 32, see
+// below); the element-wise fallback kernels give lane l the elements l, l+G,
+// l+2G, ... (G = 8 .. 64, the smallest with ceil(L/G) <= 16): there elements 2j
+// and 2j+1 sit in neighbouring lanes at the same step, and the even lane packs
+// both codes into the byte it stores.
 constexpr int kSoftmaxSlots = 16;    // elements per lane at most
 constexpr int kSoftmaxMaxL = 64 * kSoftmaxSlots;
 
@@ -727,7 +728,7 @@ __device__ __forceinline__ T group_reduce(T v, F f)
 {
     v = f(v, dpp_move<kDppXor1>(v));
     v = f(v, dpp_move<kDppXor2>(v));
-    v = f(v, dpp_move<kDppHalfMirror>(v));
+    if (G >= 8) v = f(v, dpp_move<kDppHalfMirror>(v));
     if (G >= 16) v = f(v, dpp_move<kDppMirror>(v));
     if (G >= 32) v = f(v, __shfl_xor(v, 16, kWave));
     if (G >= 64) v = f(v, __shfl_xor(v, 32, kWave));
@@ -789,7 +790,7 @@ __device__ __forceinline__ void copy_unit(unsigned char* dst, const unsigned cha
     else if (UNIT == 2) *(uint16_t*)dst = *(const uint16_t*)src;
     else *dst = *src;
 }
-template <int UNIT>
+template <int UNIT, int BLOCK>
 __device__ __forceinline__ void stage_in(const void* src, unsigned char* lds, int64_t a, int64_t b,
                                          int64_t total)
 {
@@ -800,18 +801,21 @@ __device__ __forceinline__ void stage_in(const void* src, unsigned char* lds, in
     const bool cut = a_dn + 16 * (int64_t)nv > total;            // the tensor ends inside the last vector
     const int nfull = cut ? nv - 1 : nv;
     const int tid = (int)threadIdx.x;
+    // lane <-> vector mapping relative to a 256-byte aligned window, so that every
+    // wave-wide access covers whole, aligned lines except at the two ends of the span
+    const int i0 = (int)(((uintptr_t)g0 >> 4) & 15);
     constexpr int U = 4;
-    for (int base = 0; base < nfull; base += U * kSoftmaxBlock) {
+    for (int base = -i0; base < nfull; base += U * BLOCK) {
         u32x4 t[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = base + u * kSoftmaxBlock + tid;
-            if (i < nfull) t[u] = stream_load128((const u32x4*)(g0 + 16 * i));
+            const int i = base + u * BLOCK + tid;
+            if (i >= 0 && i < nfull) t[u] = stream_load128((const u32x4*)(g0 + 16 * i));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = base + u * kSoftmaxBlock + tid;
-            if (i < nfull) *(u32x4*)(lds + 16 * i) = t[u];
+            const int i = base + u * BLOCK + tid;
+            if (i >= 0 && i < nfull) *(u32x4*)(lds + 16 * i) = t[u];
         }
     }
     if (cut && tid < 16 / UNIT) {
@@ -822,7 +826,7 @@ __device__ __forceinline__ void stage_in(const void* src, unsigned char* lds, in
 // The reverse copy.  Vectors that lie wholly inside [a, b) are stored as such;
 // the ragged first and last vector belong partly to other blocks and are
 // written element by element, one element per lane.
-template <int UNIT>
+template <int UNIT, int BLOCK>
 __device__ __forceinline__ void stage_out(void* dst, const unsigned char* lds, int64_t a, int64_t b)
 {
     const int64_t a_dn = a & ~(int64_t)15;
@@ -830,8 +834,9 @@ __device__ __forceinline__ void stage_out(void* dst, const unsigned char* lds, i
     const int head = (int)(a - a_dn), span = (int)(b - a_dn);
     const int first_full = head ? 1 : 0, last_full = span >> 4;  // vectors [first_full, last_full) are whole
     const int tid = (int)threadIdx.x;
-    for (int i = first_full + tid; i < last_full; i += kSoftmaxBlock)
-        stream_store128((u32x4*)(g0 + 16 * i), *(const u32x4*)(lds + 16 * i));
+    const int i0 = (int)(((uintptr_t)g0 >> 4) & 15);  // 256-byte aligned windows, as in stage_in
+    for (int i = tid - i0; i < last_full; i += BLOCK)
+        if (i >= first_full) stream_store128((u32x4*)(g0 + 16 * i), *(const u32x4*)(lds + 16 * i));
     constexpr int PER = 16 / UNIT;
     if (tid < 2 * PER) {
         const bool tail = tid >= PER;
@@ -843,16 +848,38 @@ __device__ __forceinline__ void stage_out(void* dst, const unsigned char* lds, i
 
 // ---- staged kernels: x, y (dy, dx) and codes 16-byte aligned (the launcher checks) ----
 //
-// Straight-line per lane: only the last slot of a row (k = (L-1)/G) can hold
-// lanes past the row end, so every earlier slot runs without predicates; rows
-// past the end of the tensor (last block only) shadow the block's last real
-// row and send their LDS writes to a spare slot.  `data_bytes` is the size of
-// the LDS data area; the codes area follows it, and 16 spare bytes follow that.
+// A row is handled by G lanes (4, 8, 16 or 32).  Lane l owns the element PAIRS
+// l, l+G, l+2G, ... of its row (pair j = elements 2j and 2j+1), SLOTS pairs at
+// most, SLOTS = ceil(ceil(L/2) / G) exactly: the two codes of a pair share one
+// byte of the row-aligned code array, so a lane forms and stores whole bytes by
+// itself, and two outputs leave through one bf16 conversion.  Only the last
+// slot can hold lanes whose pair is half or wholly past the row end, so every
+// earlier slot runs without predicates and in straight-line code.  Rows past
+// the end of the tensor (last block only) shadow the block's last real row and
+// store nothing.  `data_bytes` is the size of the LDS data area; the codes area
+// follows it.
 
 template <bool BF16>
 __device__ __forceinline__ float lds_in(const unsigned char* p)
 {
     return BF16 ? as_f32((uint32_t)(*(const uint16_t*)p) << 16) : *(const float*)p;
+}
+// Two neighbouring elements to LDS.  Rows of odd length start on odd elements,
+// so a bf16 pair is only 2-byte aligned: two 16-bit stores of one packed word,
+// volatile so that they are not merged into one misaligned 32-bit store (which
+// the LDS accepts but serialises: measured 1.7x on the whole kernel).
+template <bool BF16>
+__device__ __forceinline__ void lds_out2(unsigned char* p, float a, float b)
+{
+    if (BF16) {
+        const uint32_t w = pack_bf16(a, b);
+        typedef volatile __attribute__((address_space(3))) uint16_t lds_u16;
+        ((lds_u16*)p)[0] = (uint16_t)w;
+        ((lds_u16*)p)[1] = (uint16_t)(w >> 16);
+    } else {
+        ((float*)p)[0] = a;
+        ((float*)p)[1] = b;
+    }
 }
 template <bool BF16>
 __device__ __forceinline__ void lds_out(unsigned char* p, float v)
@@ -860,20 +887,48 @@ __device__ __forceinline__ void lds_out(unsigned char* p, float v)
     if (BF16) *(uint16_t*)p = (uint16_t)pack_bf16(v, 0.0f); else *(float*)p = v;
 }
 
+// Three-operand maximum / minimum: one VALU op takes in both elements of a pair.
+__device__ __forceinline__ float vmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float vmin3(float a, float b, float c)
+{
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// exp(x - m) for all elements of one row.  bf16 storage: exp2(x*log2e - m*log2e)
+// with the second product formed once per row; its rounding error is the same
+// factor on every element of the row and cancels in the normalisation.  fp32
+// storage: the compensated difference of exp_diff.
+template <bool BF16>
+struct RowExp {
+    float m, nm;
+    __device__ __forceinline__ explicit RowExp(float m_) : m(m_), nm(-m_ * 1.44269504088896340736f) {}
+    __device__ __forceinline__ float operator()(float x) const
+    {
+        if (BF16) return __builtin_amdgcn_exp2f(__builtin_fmaf(x, 1.44269504088896340736f, nm));
+        return exp_diff<false>(x, m);
+    }
+};
+
 // PASSES = row groups per block: more bytes in flight per block, fewer blocks.
-// SLOTS = slots compiled in (>= (L-1)/G + 1): the unrolled slot loops are turned
-// into selects by the compiler, so every compiled slot costs its arithmetic
-// whether the row reaches it or not; the launcher picks the smallest bucket.
-template <bool BF16, int G, int PASSES, int SLOTS>
-__global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* x, void* y,
+template <bool BF16, int G, int PASSES, int SLOTS, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void softmax_fwd_staged(const void* x, void* y,
                                                                     uint8_t* codes,
                                                                     float* __restrict__ qparams,
                                                                     int64_t rows, int L,
-                                                                    int data_bytes, int codes_bytes)
+                                                                    int data_bytes)
 {
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr int RPP = kSoftmaxBlock / G;           // rows per pass
+    constexpr int RPP = BLOCK / G;   // rows per pass
     constexpr int RPB = RPP * PASSES;        // rows per block
+    constexpr int KL = SLOTS - 1;            // the only slot that can be partly empty
+    constexpr int PS = 2 * G * ES;           // bytes between a lane's consecutive pairs
     extern __shared__ __align__(16) unsigned char lds[];
     const int l = threadIdx.x % G;
     const int64_t row0 = (int64_t)blockIdx.x * RPB;
@@ -881,110 +936,111 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_staged(const void* 
     const int rb = (L + 1) / 2;
     const int64_t xa = row0 * L * ES, xb = (row0 + nrows) * L * ES;
     const int64_t ca = row0 * rb, cb = (row0 + nrows) * rb;
-    unsigned char* spare = lds + data_bytes + codes_bytes;
-    const int klast = (L - 1) / G;            // the only slot that can be partly empty
-    const int ilast = l + klast * G;          // this lane's element index in that slot
-    const bool has_last = ilast < L;
-    const float ninf = -__builtin_inff(), pinf = __builtin_inff();
-    const int own_shift = (l & 1) * 4, other_shift = 4 - own_shift;
+    const int e0 = 2 * (l + KL * G), e1 = e0 + 1;  // this lane's elements in the last slot
+    const bool has0 = e0 < L, has1 = e1 < L;
+    // lanes past the row end re-read the row's last element: a duplicate changes neither extreme
+    const int o0 = ((has0 ? e0 : L - 1) - 2 * l) * ES, o1 = ((has1 ? e1 : L - 1) - 2 * l) * ES;
 
-    stage_in<ES>(x, lds, xa, xb, rows * L * ES);
+    stage_in<ES, BLOCK>(x, lds, xa, xb, rows * L * ES);
     __syncthreads();
 
 #pragma unroll 1
     for (int pass = 0; pass < PASSES; ++pass) {
-    const int lrow = pass * RPP + (int)threadIdx.x / G;
-    const bool live = lrow < nrows;
-    const int srow = live ? lrow : nrows - 1;  // dead lanes shadow the last real row
-    // this lane's element of slot 0, and the byte its pair shares, inside LDS
-    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + l) * ES;
-    unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
+        const int lrow = pass * RPP + (int)threadIdx.x / G;
+        const bool live = lrow < nrows;
+        const int srow = live ? lrow : nrows - 1;
+        unsigned char* lx = lds + (int)(xa & 15) + (srow * L + 2 * l) * ES;  // this lane's first pair
+        unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + l;  // and its code byte
 
-    // pass 1: load, row maximum and minimum
-    float v[SLOTS];
-    float m = ninf, xmin = pinf;
+        // pass 1: load, row maximum and minimum
+        float a[SLOTS], b[SLOTS];
+        float m = -__builtin_inff(), xmin = __builtin_inff();
 #pragma unroll
-    for (int k = 0; k < SLOTS - 1; ++k)
-        if (k < klast) {
-            v[k] = lds_in<BF16>(lx + k * G * ES);
-            m = vmax(m, v[k]);
-            xmin = vmin(xmin, v[k]);
+        for (int k = 0; k < KL; ++k) {
+            a[k] = lds_in<BF16>(lx + k * PS);
+            b[k] = lds_in<BF16>(lx + k * PS + ES);
         }
-    float vl = lds_in<BF16>(lx + ((has_last ? ilast : L - 1) - l) * ES);
-    m = vmax(m, has_last ? vl : ninf);
-    xmin = vmin(xmin, has_last ? vl : pinf);
-    m = group_max<G>(m);
-    xmin = group_min<G>(xmin);
+        a[KL] = lds_in<BF16>(lx + o0);
+        b[KL] = lds_in<BF16>(lx + o1);
+#pragma unroll
+        for (int k = 0; k < SLOTS; ++k) {
+            m = vmax3(m, a[k], b[k]);
+            xmin = vmin3(xmin, a[k], b[k]);
+        }
+        m = group_max<G>(m);
+        xmin = group_min<G>(xmin);
 
-    // pass 2: exponentials and their sum
-    typedef typename std::conditional<BF16, float, double>::type acc_t;
-    acc_t sum = 0;
+        // pass 2: exponentials and their sum
+        const RowExp<BF16> ex(m);
+        typedef typename std::conditional<BF16, float, double>::type acc_t;
+        acc_t sum = 0;
 #pragma unroll
-    for (int k = 0; k < SLOTS - 1; ++k)
-        if (k < klast) {
-            v[k] = exp_diff<BF16>(v[k], m);
-            sum += (acc_t)v[k];
+        for (int k = 0; k < KL; ++k) {
+            a[k] = ex(a[k]);
+            b[k] = ex(b[k]);
+            sum += (acc_t)a[k];
+            sum += (acc_t)b[k];
         }
-    vl = has_last ? exp_diff<BF16>(vl, m) : 0.0f;
-    sum += (acc_t)vl;
-    sum = group_sum<G>(sum);
-    // reciprocals by v_rcp_f32 (1 ulp): a full division sequence costs a dozen instructions per lane
-    const float inv = BF16 ? __builtin_amdgcn_rcpf((float)sum) : (float)((acc_t)1 / sum);
-    // y is monotone in x, so its extremes are the images of the row's extremes
-    const float hi = exp_diff<BF16>(m, m) * inv;
-    const float lo = exp_diff<BF16>(xmin, m) * inv;
-    const float scale = (hi - lo) * (1.0f / 15.0f);
-    const float inv_scale = hi > lo ? 15.0f * __builtin_amdgcn_rcpf(hi - lo) : 0.0f;
-    if (live && l == 0) {
-        qparams[2 * (row0 + lrow)] = lo;
-        qparams[2 * (row0 + lrow) + 1] = scale;
-    }
+        a[KL] = has0 ? ex(a[KL]) : 0.0f;
+        b[KL] = has1 ? ex(b[KL]) : 0.0f;
+        sum += (acc_t)a[KL];
+        sum += (acc_t)b[KL];
+        sum = group_sum<G>(sum);
+        // reciprocals by v_rcp_f32 (1 ulp): a full division sequence costs a dozen instructions per lane
+        const float inv = BF16 ? __builtin_amdgcn_rcpf((float)sum) : (float)((acc_t)1 / sum);
+        // y is monotone in x, so its extremes are the images of the row's extremes
+        const float hi = ex(m) * inv;
+        const float lo = ex(xmin) * inv;
+        const float scale = (hi - lo) * (1.0f / 15.0f);
+        const float inv_scale = hi > lo ? 15.0f * __builtin_amdgcn_rcpf(hi - lo) : 0.0f;
+        if (live && l == 0) {
+            qparams[2 * (row0 + lrow)] = lo;
+            qparams[2 * (row0 + lrow) + 1] = scale;
+        }
 
-    // pass 3: y and the codes into LDS.  Both lanes of a pair form the same byte
-    // and write it to the same place.
-    auto quantize = [&](float yk) -> uint32_t {
-        float t = __builtin_fmaf(yk - lo, inv_scale, 0.5f);
-        uint32_t c;
-        asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));  // floor; NaN and negatives -> 0
-        return c < 15u ? c : 15u;
-    };
-    unsigned char* wy = live ? lx : spare;   // dead rows write to the spare slot
-    unsigned char* wc = live ? lc : spare;
-    const int ystep = live ? G * ES : 0, cstep = live ? G / 2 : 0;
+        // pass 3: y and the codes into LDS.  lo <= y <= hi and inv_scale is
+        // 15/(hi - lo) to 1 ulp, so (y - lo)*inv_scale + 0.5 stays below 15.5*(1 + 2^-22):
+        // the saturating conversion (floor; NaN and negatives -> 0) never exceeds 15.
+        auto quantize = [&](float yk) -> uint32_t {
+            float t = __builtin_fmaf(yk - lo, inv_scale, 0.5f);
+            uint32_t c;
+            asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));
+            return c;
+        };
+        if (live) {
 #pragma unroll
-    for (int k = 0; k < SLOTS - 1; ++k)
-        if (k < klast) {
-            const float yk = v[k] * inv;
-            const uint32_t c = quantize(yk);
-            const uint32_t other = (uint32_t)dpp_move<kDppXor1>((int)c);
-            lds_out<BF16>(wy + k * ystep, yk);
-            wc[k * cstep] = (uint8_t)((c << own_shift) | (other << other_shift));
+            for (int k = 0; k < KL; ++k) {
+                const float ya = a[k] * inv, yb = b[k] * inv;
+                lds_out2<BF16>(lx + k * PS, ya, yb);
+                lc[k * G] = (uint8_t)(quantize(ya) | (quantize(yb) << 4));
+            }
+            const float ya = a[KL] * inv, yb = b[KL] * inv;
+            if (has1) {
+                lds_out2<BF16>(lx + KL * PS, ya, yb);
+                lc[KL * G] = (uint8_t)(quantize(ya) | (quantize(yb) << 4));
+            } else if (has0) {  // the row's last, unpaired element: the pad nibble is 0
+                lds_out<BF16>(lx + KL * PS, ya);
+                lc[KL * G] = (uint8_t)quantize(ya);
+            }
         }
-    {
-        const float yk = vl * inv;
-        const uint32_t c = has_last ? quantize(yk) : 0u;  // 0 = pad nibble
-        const uint32_t other = (uint32_t)dpp_move<kDppXor1>((int)c);
-        // a lane past the row end still writes the shared byte if its partner is the row's last element
-        const bool byte_in_row = (ilast & ~1) < L;
-        lds_out<BF16>(live && has_last ? lx + klast * G * ES : spare, yk);
-        *(live && byte_in_row ? lc + klast * (G / 2) : spare) = (uint8_t)((c << own_shift) | (other << other_shift));
-    }
     }  // pass
     __syncthreads();
-    stage_out<ES>(y, lds, xa, xb);
-    stage_out<1>(codes, lds + data_bytes, ca, cb);
+    stage_out<ES, BLOCK>(y, lds, xa, xb);
+    stage_out<1, BLOCK>(codes, lds + data_bytes, ca, cb);
 }
 
-template <bool BF16, int G, int PASSES, int SLOTS>
-__global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* dy,
+template <bool BF16, int G, int PASSES, int SLOTS, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void softmax_bwd_staged(const void* dy,
                                                                     const uint8_t* codes,
                                                                     const float* __restrict__ qparams,
                                                                     void* dx, int64_t rows, int L,
-                                                                    int data_bytes, int codes_bytes)
+                                                                    int data_bytes)
 {
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr int RPP = kSoftmaxBlock / G;
+    constexpr int RPP = BLOCK / G;
     constexpr int RPB = RPP * PASSES;
+    constexpr int KL = SLOTS - 1;
+    constexpr int PS = 2 * G * ES;
     extern __shared__ __align__(16) unsigned char lds[];
     const int l = threadIdx.x % G;
     const int64_t row0 = (int64_t)blockIdx.x * RPB;
@@ -992,53 +1048,57 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_staged(const void* 
     const int rb = (L + 1) / 2;
     const int64_t xa = row0 * L * ES, xb = (row0 + nrows) * L * ES;
     const int64_t ca = row0 * rb, cb = (row0 + nrows) * rb;
-    unsigned char* spare = lds + data_bytes + codes_bytes;
-    const int klast = (L - 1) / G;
-    const int ilast = l + klast * G;
-    const bool has_last = ilast < L;
-    const int nib_shift = (l & 1) * 4;
+    const int e0 = 2 * (l + KL * G), e1 = e0 + 1;
+    const bool has0 = e0 < L, has1 = e1 < L;
+    // lanes past the row end read the row's last element and last byte, and drop them
+    const int o0 = ((has0 ? e0 : L - 1) - 2 * l) * ES, o1 = ((has1 ? e1 : L - 1) - 2 * l) * ES;
+    const int oc = (has0 ? l + KL * G : rb - 1) - l;
 
-    stage_in<ES>(dy, lds, xa, xb, rows * L * ES);
-    stage_in<1>(codes, lds + data_bytes, ca, cb, rows * rb);
+    stage_in<ES, BLOCK>(dy, lds, xa, xb, rows * L * ES);
+    stage_in<1, BLOCK>(codes, lds + data_bytes, ca, cb, rows * rb);
     __syncthreads();
 
 #pragma unroll 1
     for (int pass = 0; pass < PASSES; ++pass) {
-    const int lrow = pass * RPP + (int)threadIdx.x / G;
-    const bool live = lrow < nrows;
-    const int srow = live ? lrow : nrows - 1;
-    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + l) * ES;
-    const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + (l >> 1);
-    const float lo = qparams[2 * (row0 + srow)];
-    const float scale = qparams[2 * (row0 + srow) + 1];
+        const int lrow = pass * RPP + (int)threadIdx.x / G;
+        const bool live = lrow < nrows;
+        const int srow = live ? lrow : nrows - 1;
+        unsigned char* lx = lds + (int)(xa & 15) + (srow * L + 2 * l) * ES;
+        const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + l;
+        const float lo = qparams[2 * (row0 + srow)];
+        const float scale = qparams[2 * (row0 + srow) + 1];
 
-    auto dequant = [&](uint32_t byte) { return __builtin_fmaf((float)((byte >> nib_shift) & 15u), scale, lo); };
-    float yh[SLOTS], g[SLOTS];
-    float dot = 0.0f;
+        float ya[SLOTS], yb[SLOTS], ga[SLOTS], gb[SLOTS];
 #pragma unroll
-    for (int k = 0; k < SLOTS - 1; ++k)
-        if (k < klast) {
-            yh[k] = dequant(lc[k * (G / 2)]);
-            g[k] = lds_in<BF16>(lx + k * G * ES);
-            dot = __builtin_fmaf(yh[k], g[k], dot);
+        for (int k = 0; k < SLOTS; ++k) {
+            const uint32_t byte = lc[k < KL ? k * G : oc];
+            ya[k] = __builtin_fmaf((float)(byte & 15u), scale, lo);
+            yb[k] = __builtin_fmaf((float)(byte >> 4), scale, lo);
+            ga[k] = lds_in<BF16>(lx + (k < KL ? k * PS : o0));
+            gb[k] = lds_in<BF16>(lx + (k < KL ? k * PS + ES : o1));
         }
-    const int sl = (has_last ? ilast : L - 1) - l;  // a safe element for lanes past the row end
-    float yl = dequant(lc[(has_last ? klast * (G / 2) : ((L - 1) >> 1) - (l >> 1))]);
-    float gl = lds_in<BF16>(lx + sl * ES);
-    yl = has_last ? yl : 0.0f;
-    gl = has_last ? gl : 0.0f;
-    dot = __builtin_fmaf(yl, gl, dot);
-    dot = group_sum<G>(dot);
-
-    unsigned char* wx = live ? lx : spare;
-    const int xstep = live ? G * ES : 0;
+        float dot = 0.0f;
 #pragma unroll
-    for (int k = 0; k < SLOTS - 1; ++k)
-        if (k < klast) lds_out<BF16>(wx + k * xstep, yh[k] * (g[k] - dot));
-    lds_out<BF16>(live && has_last ? lx + klast * G * ES : spare, yl * (gl - dot));
+        for (int k = 0; k < KL; ++k) {
+            dot = __builtin_fmaf(ya[k], ga[k], dot);
+            dot = __builtin_fmaf(yb[k], gb[k], dot);
+        }
+        dot = has0 ? __builtin_fmaf(ya[KL], ga[KL], dot) : dot;
+        dot = has1 ? __builtin_fmaf(yb[KL], gb[KL], dot) : dot;
+        dot = group_sum<G>(dot);
+
+        if (live) {
+#pragma unroll
+            for (int k = 0; k < KL; ++k)
+                lds_out2<BF16>(lx + k * PS, ya[k] * (ga[k] - dot), yb[k] * (gb[k] - dot));
+            if (has1)
+                lds_out2<BF16>(lx + KL * PS, ya[KL] * (ga[KL] - dot), yb[KL] * (gb[KL] - dot));
+            else if (has0)
+                lds_out<BF16>(lx + KL * PS, ya[KL] * (ga[KL] - dot));
+        }
     }  // pass
     __syncthreads();
-    stage_out<ES>(dx, lds, xa, xb);
+    stage_out<ES, BLOCK>(dx, lds, xa, xb);
 }
 
 // ---- element-wise kernels for buffers that are not 16-byte aligned (same results, not tuned) ----
