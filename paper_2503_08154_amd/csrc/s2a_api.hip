@@ -567,22 +567,28 @@ int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t 
     if (!x || !y || !A || !B) return S2A_ERR_NULL;
     if (!aligned(x, 16) || !aligned(y, 16) || !aligned(A, 4) || !aligned(B, 4)) return S2A_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    // about 800 blocks fill the chip; a block re-reads B (r*C floats, from L2) once per batch chunk,
-    // so chunks are kept at 8 samples or more
-    int chunks = (int)((800 + N - 1) / N);
-    if (chunks > (batch + 7) / 8) chunks = (int)((batch + 7) / 8);
-    if (chunks < 1) chunks = 1;
-    if (chunks > 65535) chunks = 65535;
-    const int per = (int)((batch + chunks - 1) / chunks);
-    chunks = (int)((batch + per - 1) / per);
-    dim3 grid((unsigned)N, (unsigned)chunks);
+    // a lane owns one vector position of the sample and a chunk of the batch: chunks of 8 samples
+    // (eight loads in flight, the prompt values formed once per 8) unless that leaves the chip short of lanes
+    const int epv = dtype == S2A_BF16 ? 8 : 4;
+    const int64_t sample = N * (C / epv);               // vectors per sample
+    const int64_t blocks = (sample + s2a::kLrpBlock - 1) / s2a::kLrpBlock;
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    int64_t per = 8;
+    while (per > 2 && sample * ((batch + per - 1) / per) < 128 * 1024) per /= 2;
+    int64_t chunks = (batch + per - 1) / per;
+    if (chunks > 65535) {
+        chunks = 65535;
+        per = (batch + chunks - 1) / chunks;
+        chunks = (batch + per - 1) / per;
+    }
+    dim3 grid((unsigned)blocks, (unsigned)chunks);
     return checked_launch([&] {
         if (dtype == S2A_BF16)
             s2a::lrp_fwd_kernel<true><<<grid, dim3(s2a::kLrpBlock), 0, st>>>(
-                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r, per);
+                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r, (int)per);
         else
             s2a::lrp_fwd_kernel<false><<<grid, dim3(s2a::kLrpBlock), 0, st>>>(
-                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r, per);
+                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r, (int)per);
     });
 }
 
@@ -597,28 +603,23 @@ int s2a_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float
         return S2A_ERR_ALIGN;
     if (N > 0x7fffffff) return S2A_ERR_SIZE;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t sample_words = dtype == S2A_BF16 ? N * C / 2 : N * C;
-    const int64_t blocks = (sample_words + s2a::kLrpBlock - 1) / s2a::kLrpBlock;
-    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    // LDS of the first kernel: S partial rows and the summed row of one chunk of channels
+    const int epv = dtype == S2A_BF16 ? 8 : 4;
+    const int64_t vpt = C / epv;
+    const int64_t cv = vpt < s2a::kLrpTokenBlock ? vpt : s2a::kLrpTokenBlock;
+    const size_t lds = (size_t)((s2a::kLrpTokenBlock / cv) * cv + cv) * epv * sizeof(float);
     rc = checked_launch([&] {
         if (dtype == S2A_BF16)
-            s2a::lrp_batch_sum_kernel<true><<<dim3((unsigned)blocks), dim3(s2a::kLrpBlock), 0, st>>>(
-                (const uint32_t*)dy, work, (int)batch, sample_words);
+            s2a::lrp_grad_token_kernel<true><<<dim3((unsigned)N), dim3(s2a::kLrpTokenBlock), lds, st>>>(
+                (const s2a::u32x4*)dy, B, work, dA, (int)batch, (int)N, (int)C, r);
         else
-            s2a::lrp_batch_sum_kernel<false><<<dim3((unsigned)blocks), dim3(s2a::kLrpBlock), 0, st>>>(
-                (const uint32_t*)dy, work, (int)batch, sample_words);
-    });
-    if (rc != S2A_OK) return rc;
-    rc = checked_launch([&] {
-        if (r <= 8) s2a::lrp_grad_a_kernel<8><<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
-        else if (r <= 16) s2a::lrp_grad_a_kernel<16><<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
-        else if (r <= 32) s2a::lrp_grad_a_kernel<32><<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
-        else s2a::lrp_grad_a_kernel<64><<<dim3((unsigned)N), dim3(s2a::kLrpBlock), 0, st>>>(work, B, dA, (int)C, r);
+            s2a::lrp_grad_token_kernel<false><<<dim3((unsigned)N), dim3(s2a::kLrpTokenBlock), lds, st>>>(
+                (const s2a::u32x4*)dy, B, work, dA, (int)batch, (int)N, (int)C, r);
     });
     if (rc != S2A_OK) return rc;
     return checked_launch([&] {
         s2a::lrp_grad_b_kernel<<<dim3((unsigned)((C + s2a::kWave - 1) / s2a::kWave), (unsigned)r),
-                                 dim3(s2a::kLrpBlock), 0, st>>>(work, A, dB, (int)N, (int)C, r);
+                                 dim3(s2a::kLrpGradBBlock), 0, st>>>(work, A, dB, (int)N, (int)C, r);
     });
 }
 

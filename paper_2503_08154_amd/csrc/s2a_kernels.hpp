@@ -1338,16 +1338,20 @@ __global__ __launch_bounds__(kBlock) void cap_bwd_kernel_unaligned(const void* d
 // the batch; dL/dx = dL/dy, dL/dA = dL/dy B^T, dL/dB = A^T dL/dy, both summed
 // over the batch.  Neither x nor y is needed in backward.
 //
-// Forward: the prompt is never materialised.  A block owns one token i and a
-// chunk of the batch; each lane owns 16-byte vectors of channels, forms its
-// EPV prompt values P[i, c..] = sum_k A[i,k] B[k,c..] once (A[i,:] is uniform
-// over the block, B comes from L2) and then streams x -> y over its batch
-// chunk with eight loads in flight.  HBM traffic: x once, y once.
-// Backward: G = sum_b dL/dy[b] is formed once (a streaming pass over dL/dy,
-// fp32, into a caller-provided N*C workspace), then dA = G B^T (one block per
-// token) and dB = A^T G (one lane per (k, c)); the two products are tiny
-// (N*C*r = 4.5 MFLOP at ViT-B/16) next to the pass over dL/dy.
+// Forward: the prompt is never materialised in HBM.  A lane owns one 16-byte
+// vector position of the sample (token i, channels c..c+EPV-1) and a chunk of
+// the batch: it forms its EPV prompt values P[i, c..] = sum_k A[i,k] B[k,c..]
+// once (A and B come from L2, eight rows of B in flight) and then streams x ->
+// y over its batch chunk with eight 16-byte loads in flight.  A sample holds
+// only ~150 k elements, so the batch chunks are what fills the chip.  HBM
+// traffic: x once, y once.
+//
+// Backward: G = sum_b dL/dy[b] and dA = G B^T come from one kernel (one block
+// per token, one pass over dL/dy; G goes to a caller-provided N*C fp32
+// workspace), dB = A^T G from a second; the two products are tiny (N*C*r =
+// 4.5 MFLOP at ViT-B/16) next to the pass over dL/dy.
 constexpr int kLrpBlock = 256;
+constexpr int kLrpTokenBlock = 1024;
 constexpr int kLrpMaxRank = 64;
 
 template <bool BF16>
@@ -1358,139 +1362,185 @@ __global__ __launch_bounds__(kLrpBlock) void lrp_fwd_kernel(const u32x4* x, u32x
                                                             int batch_chunk)
 {
     constexpr int EPV = BF16 ? 8 : 4;
-    const int i = blockIdx.x;  // token
+    const int vpt = C / EPV;                            // vectors per token row (the launcher checks C % EPV)
+    const int64_t sample = (int64_t)N * vpt;            // vectors per sample
+    const int64_t at = (int64_t)blockIdx.x * kLrpBlock + threadIdx.x;  // this lane's vector inside a sample
+    if (at >= sample) return;
+    const int i = (int)(at / vpt), c0 = (int)(at - (int64_t)i * vpt) * EPV;
     const int b0 = blockIdx.y * batch_chunk;
     const int b1 = b0 + batch_chunk < batch ? b0 + batch_chunk : batch;
-    const int cvecs = C / EPV;  // C is a multiple of EPV (the launcher checks)
+    constexpr int U = 8;
+    // the first round of x is requested before the prompt values are formed: the two latencies overlap
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (b0 + u < b1) v[u] = stream_load128(x + (b0 + u) * sample + at);
     const float* Ai = A + (int64_t)i * r;
-    for (int cv = threadIdx.x; cv < cvecs; cv += kLrpBlock) {
-        float p[EPV];
+    const float* Bc = B + c0;
+    float p[EPV];
 #pragma unroll
-        for (int j = 0; j < EPV; ++j) p[j] = 0.0f;
-        for (int k = 0; k < r; ++k) {
-            const float a = Ai[k];
-            const float* Bk = B + (int64_t)k * C + cv * EPV;
+    for (int j = 0; j < EPV; ++j) p[j] = 0.0f;
+    constexpr int KU = 8;
+    int k = 0;
+    const bool b_vectors = ((uintptr_t)B & 15u) == 0;  // C and c0 are multiples of EPV, so rows follow B
+    for (; b_vectors && k < r; k += KU) {  // KU rows of B in flight; each sum keeps its order in k
+        u32x4 bk[KU][EPV / 4];
+        float a[KU];
 #pragma unroll
-            for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a, Bk[j], p[j]);
-        }
-        const int64_t sample = (int64_t)N * cvecs;          // vectors per sample
-        const int64_t at = (int64_t)i * cvecs + cv;          // this lane's vector inside a sample
-        constexpr int U = 8;
-        for (int b = b0; b < b1; b += U) {
-            u32x4 v[U];
+        for (int u = 0; u < KU; ++u)
+            if (k + u < r) {
+                a[u] = Ai[k + u];
+#pragma unroll
+                for (int h = 0; h < EPV / 4; ++h) bk[u][h] = *(const u32x4*)(Bc + (int64_t)(k + u) * C + 4 * h);
+            }
+#pragma unroll
+        for (int u = 0; u < KU; ++u)
+            if (k + u < r) {
+#pragma unroll
+                for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a[u], as_f32(bk[u][j / 4][j % 4]), p[j]);
+            }
+    }
+    for (; k < r; ++k) {  // B not 16-byte aligned: element loads
+        const float a = Ai[k];
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a, Bc[(int64_t)k * C + j], p[j]);
+    }
+    for (int b = b0; b < b1; b += U) {
+        if (b != b0) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (b + u < b1) v[u] = stream_load128(x + (b + u) * sample + at);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (b + u < b1) {
-                    float f[EPV];
-                    unpack_vector<BF16>(v[u], f);
-                    u32x4 o;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        o[j] = BF16 ? pack_bf16(f[2 * j] + p[2 * j], f[2 * j + 1] + p[2 * j + 1]) : as_u32(f[j] + p[j]);
-                    stream_store128(y + (b + u) * sample + at, o);
-                }
         }
-    }
-}
-
-// G[i, c] = sum_b dy[b, i, c], fp32.  One lane per dword of a sample (two bf16
-// or one fp32): a sample is only ~150 k elements, so narrow lanes are what
-// fills the chip; eight loads per lane are in flight.
-template <bool BF16>
-__global__ __launch_bounds__(kLrpBlock) void lrp_batch_sum_kernel(const uint32_t* dy,
-                                                                  float* __restrict__ G, int batch,
-                                                                  int64_t sample_words)
-{
-    const int64_t at = (int64_t)blockIdx.x * kLrpBlock + threadIdx.x;
-    if (at >= sample_words) return;
-    float acc0 = 0.0f, acc1 = 0.0f;
-    constexpr int U = 8;
-    for (int b = 0; b < batch; b += U) {
-        uint32_t w[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (b + u < batch) w[u] = stream_load32(dy + (b + u) * sample_words + at);
+            if (b + u < b1) {
+                float f[EPV];
+                unpack_vector<BF16>(v[u], f);
+                u32x4 o;
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (b + u < batch) {
-                if (BF16) {
-                    acc0 += bf16_lo(w[u]);
-                    acc1 += bf16_hi(w[u]);
-                } else {
-                    acc0 += as_f32(w[u]);
-                }
+                for (int j = 0; j < 4; ++j)
+                    o[j] = BF16 ? pack_bf16(f[2 * j] + p[2 * j], f[2 * j + 1] + p[2 * j + 1]) : as_u32(f[j] + p[j]);
+                stream_store128(y + (b + u) * sample + at, o);
             }
     }
-    if (BF16) {
-        G[2 * at] = acc0;
-        G[2 * at + 1] = acc1;
-    } else {
-        G[at] = acc0;
+}
+
+// Backward, first kernel: one block of kLrpTokenBlock lanes per token i.
+//   G[i, c]  = sum_b dy[b, i, c]            (fp32, written to the workspace)
+//   dA[i, k] = sum_c G[i, c] B[k, c]
+// A sample holds only ~150 k elements, so the batch is what fills the chip: the
+// token's channel vectors are spread over the lanes S times, copy s summing the
+// samples s, s+S, s+2S, ... with eight 16-byte loads in flight, and the S
+// partial rows meet in LDS (fixed order, so the result does not depend on the
+// launch).  The row of G then stays in LDS for the products with B: lane
+// (k, q) of 32 x 32 takes channels q, q+32, ... of prompt row k, and the 32
+// partial sums of a k are added by cross-lane moves.  Rows wider than
+// kLrpTokenBlock vectors are taken in chunks.
+
+template <bool BF16>
+__global__ __launch_bounds__(kLrpTokenBlock) void lrp_grad_token_kernel(const u32x4* dy,
+                                                                        const float* __restrict__ B,
+                                                                        float* __restrict__ G,
+                                                                        float* __restrict__ dA,
+                                                                        int batch, int N, int C, int r)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    extern __shared__ __align__(16) float lrp_lds[];
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const int vpt = C / EPV;                           // vectors per token row
+    const int64_t sample = (int64_t)N * vpt;           // vectors per sample
+    const int kq = tid & 31, kk = tid >> 5;            // the (k, q) role of the second half
+    float da0 = 0.0f, da1 = 0.0f;                      // prompt rows kk and kk + 32
+
+    for (int v0 = 0; v0 < vpt; v0 += kLrpTokenBlock) {
+        const int cv = vpt - v0 < kLrpTokenBlock ? vpt - v0 : kLrpTokenBlock;  // vectors in this chunk
+        const int S = kLrpTokenBlock / cv;             // copies of the chunk over the lanes
+        const int cc = cv * EPV;                       // channels in this chunk
+        float* part = lrp_lds;                         // [S][cc]
+        float* grow = lrp_lds + S * cc;                // [cc]
+        const int s = tid / cv, v = tid - s * cv;
+        if (s < S) {
+            float acc[EPV];
+#pragma unroll
+            for (int j = 0; j < EPV; ++j) acc[j] = 0.0f;
+            const u32x4* src = dy + (int64_t)i * vpt + v0 + v;
+            constexpr int U = 8;
+            for (int b0 = s; b0 < batch; b0 += S * U) {
+                u32x4 t[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (b0 + u * S < batch) t[u] = stream_load128(src + (int64_t)(b0 + u * S) * sample);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (b0 + u * S < batch) {
+                        float f[EPV];
+                        unpack_vector<BF16>(t[u], f);
+#pragma unroll
+                        for (int j = 0; j < EPV; ++j) acc[j] += f[j];
+                    }
+            }
+#pragma unroll
+            for (int j = 0; j < EPV; ++j) part[s * cc + v * EPV + j] = acc[j];
+        }
+        __syncthreads();
+        for (int c = tid; c < cc; c += kLrpTokenBlock) {
+            float g = 0.0f;
+            for (int q = 0; q < S; ++q) g += part[q * cc + c];
+            grow[c] = g;
+            G[(int64_t)i * C + v0 * EPV + c] = g;
+        }
+        __syncthreads();
+        const float* Bc = B + v0 * EPV;
+        auto dot_row = [&](int k, float acc) {  // eight loads of B in flight
+            const float* Bk = Bc + (int64_t)k * C;
+            int c = kq;
+            for (; c + 7 * 32 < cc; c += 8 * 32) {
+                float bk[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) bk[u] = Bk[c + 32 * u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc = __builtin_fmaf(grow[c + 32 * u], bk[u], acc);
+            }
+            for (; c < cc; c += 32) acc = __builtin_fmaf(grow[c], Bk[c], acc);
+            return acc;
+        };
+        if (kk < r) da0 = dot_row(kk, da0);
+        if (kk + 32 < r) da1 = dot_row(kk + 32, da1);
+        __syncthreads();                               // the next chunk overwrites part and grow
+    }
+    // add up the 32 lanes of a (k) group: two DPP rows of 16, then across the rows
+    auto sum32 = [](float x) {
+        x += dpp_move<kDppXor1>(x);
+        x += dpp_move<kDppXor2>(x);
+        x += dpp_move<kDppHalfMirror>(x);
+        x += dpp_move<kDppMirror>(x);
+        x += __shfl_xor(x, 16, kWave);
+        return x;
+    };
+    da0 = sum32(da0);
+    da1 = sum32(da1);
+    if (kq == 0) {
+        if (kk < r) dA[(int64_t)i * r + kk] = da0;
+        if (kk + 32 < r) dA[(int64_t)i * r + kk + 32] = da1;
     }
 }
 
-// dA[i, k] = sum_c G[i, c] B[k, c].  One block per token; every lane keeps all
-// the partial sums of its channels (RMAX >= r of them, independent chains), then
-// the sums are reduced over the wave by cross-lane moves and over the block
+// Backward, second kernel: dB[k, c] = sum_i A[i, k] G[i, c].  blockIdx.y = k; a
+// block covers 64 channels, its sixteen waves split the tokens and add up
 // through LDS.
-template <int RMAX>
-__global__ __launch_bounds__(kLrpBlock) void lrp_grad_a_kernel(const float* __restrict__ G,
-                                                               const float* __restrict__ B,
-                                                               float* __restrict__ dA, int C, int r)
+constexpr int kLrpGradBBlock = 1024;
+__global__ __launch_bounds__(kLrpGradBBlock) void lrp_grad_b_kernel(const float* __restrict__ G,
+                                                                    const float* __restrict__ A,
+                                                                    float* __restrict__ dB, int N, int C,
+                                                                    int r)
 {
-    __shared__ float part[kLrpBlock / kWave][RMAX];
-    const int i = blockIdx.x;
-    const float* Gi = G + (int64_t)i * C;
-    float acc[RMAX];
-#pragma unroll
-    for (int k = 0; k < RMAX; ++k) acc[k] = 0.0f;
-    for (int c = threadIdx.x; c < C; c += kLrpBlock) {
-        const float g = Gi[c];
-#pragma unroll
-        for (int k = 0; k < RMAX; ++k)
-            if (k < r) acc[k] = __builtin_fmaf(g, B[(int64_t)k * C + c], acc[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < RMAX; ++k) {
-        float v = acc[k];
-        v += dpp_move<kDppXor1>(v);
-        v += dpp_move<kDppXor2>(v);
-        v += dpp_move<kDppHalfMirror>(v);
-        v += dpp_move<kDppMirror>(v);
-        v += __shfl_xor(v, 16, kWave);
-        v += __shfl_xor(v, 32, kWave);
-        acc[k] = v;
-    }
-    if ((threadIdx.x & (kWave - 1)) == 0) {
-#pragma unroll
-        for (int k = 0; k < RMAX; ++k) part[threadIdx.x / kWave][k] = acc[k];
-    }
-    __syncthreads();
-    if ((int)threadIdx.x < r) {
-        float v = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kLrpBlock / kWave; ++w) v += part[w][threadIdx.x];
-        dA[(int64_t)i * r + threadIdx.x] = v;
-    }
-}
-
-// dB[k, c] = sum_i A[i, k] G[i, c].  blockIdx.y = k; a block covers 64 channels,
-// its four waves split the tokens and add up through LDS.
-__global__ __launch_bounds__(kLrpBlock) void lrp_grad_b_kernel(const float* __restrict__ G,
-                                                               const float* __restrict__ A,
-                                                               float* __restrict__ dB, int N, int C,
-                                                               int r)
-{
-    __shared__ float part[kLrpBlock / kWave][kWave];
+    constexpr int W = kLrpGradBBlock / kWave;
+    __shared__ float part[W][kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int c = blockIdx.x * kWave + lane;
     const int k = blockIdx.y;
     float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;  // independent chains
     if (c < C) {
-        constexpr int W = kLrpBlock / kWave;
         int i = wave;
         for (; i + 3 * W < N; i += 4 * W) {
             a0 = __builtin_fmaf(A[(int64_t)i * r + k], G[(int64_t)i * C + c], a0);
@@ -1505,7 +1555,7 @@ __global__ __launch_bounds__(kLrpBlock) void lrp_grad_b_kernel(const float* __re
     if (wave == 0 && c < C) {
         float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kLrpBlock / kWave; ++w) v += part[w][lane];
+        for (int w = 0; w < W; ++w) v += part[w][lane];
         dB[(int64_t)k * C + c] = v;
     }
 }
