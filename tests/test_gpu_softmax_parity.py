@@ -116,6 +116,17 @@ def test_row_lengths(dtype, L):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+def test_every_row_length(dtype):
+    """All L in 1..1024: every (lanes per row, pair slots) instantiation of the staged kernels,
+    with a row count that leaves the last block ragged; every seventh length over several blocks."""
+    for L in range(1, 1025):
+        rows = 131 if L % 7 == 0 else 3 + L % 5
+        x = _logits(rows, L, dtype, seed=40000 + L)
+        dy = wl.draw_dy(rows * L, 1.0, dtype, seed=50000 + L)
+        _run_and_check(x, dy, dtype, rows, L)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("L", [49, 197, 257])
 def test_masked_and_peaked_rows(dtype, L):
     rows = 333
