@@ -677,7 +677,7 @@ __global__ __launch_bounds__(kBlock) void relu_bwd_kernel_unaligned(const void* 
 // l+2G, ... (G = 8 .. 64, the smallest with ceil(L/G) <= 16): there elements 2j
 // and 2j+1 sit in neighbouring lanes at the same step, and the even lane packs
 // both codes into the byte it stores.
-constexpr int kSoftmaxSlots = 16;    // elements per lane at most
+constexpr int kSoftmaxSlots = 16;    // elements (fallback kernels) or element pairs (staged kernels) per lane at most
 constexpr int kSoftmaxMaxL = 64 * kSoftmaxSlots;
 
 // Cross-lane moves inside a row of 16 lanes as DPP operand modifiers (no LDS
@@ -766,16 +766,15 @@ __device__ __forceinline__ float exp_diff(float x, float m)
     return __builtin_amdgcn_exp2f(t) * __builtin_fmaf(tl, kLn2, 1.0f);
 }
 
-// Staging.  A block of kSoftmaxBlock lanes owns kSoftmaxBlock/G consecutive
-// rows, i.e. one contiguous span of x (and of y, codes).  Row starts are only
-// element-aligned (L = 197 bf16 -> 394-byte rows), so per-row access would be a
-// stream of 2-byte loads; instead the span is moved between HBM and LDS with
-// 16-byte vectors (its ragged first and last vector element by element), and the
-// row-shaped access pattern hits LDS.  The LDS copy keeps the span's offset
-// within its first 16-byte vector, so global vectors map onto aligned LDS
-// vectors.  Measured at the ViT-B/16 attention shape: 24 % -> see the design
-// notes for the staged figure.
-constexpr int kSoftmaxBlock = 256;
+// Staging.  A block of BLOCK lanes owns BLOCK/G consecutive rows, i.e. one
+// contiguous span of x (and of y, codes).  Row starts are only element-aligned
+// (L = 197 bf16 -> 394-byte rows), so per-row global access would be a stream of
+// 2-byte loads (24 % of the HBM peak at the ViT-B/16 attention shape); instead
+// the span is moved between HBM and LDS with 16-byte vectors (its ragged first
+// and last vector element by element), and the row-shaped access pattern hits
+// LDS.  The LDS copy keeps the span's offset within its first 16-byte vector,
+// so global vectors map onto aligned LDS vectors.
+constexpr int kSoftmaxBlock = 256;  // lanes per block of the fallback kernels
 
 // Copy bytes [a, b) of `src` (global, `total` bytes long, 16-byte aligned) to
 // lds + (p - (a & ~15)).  Whole 16-byte vectors are moved, including the first
