@@ -25,7 +25,7 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _check(batch, N, C, r, dtype, seed, inplace=False):
+def _check(batch, N, C, r, dtype, seed, inplace=False, b_offset=0):
     g = np.random.Generator(np.random.Philox(seed))
     A = (g.standard_normal((N, r)) * 0.5).astype(np.float32)
     B = (g.standard_normal((r, C)) * 0.5).astype(np.float32)
@@ -34,7 +34,9 @@ def _check(batch, N, C, r, dtype, seed, inplace=False):
     dy = wl.draw_dy(n, 1e-2, dtype, seed=seed + 2)
     es = gu.esize(dtype)
     st = torch.cuda.current_stream().cuda_stream
-    tA, tB = _dev(A), _dev(B)
+    tA = _dev(A)
+    tB = torch.empty(r * C + b_offset, dtype=torch.float32, device="cuda")[b_offset:]   # b_offset floats off 16-byte alignment
+    tB.copy_(torch.from_numpy(B.reshape(-1)))
     bx = gu.Buf(n * es).upload(x)
     by = bx if inplace else gu.Buf(n * es, fill=0xFF)
     s2a.lrp_fwd(bx.ptr, by.ptr, tA.data_ptr(), tB.data_ptr(), batch, N, C, r, dtype, st)
@@ -71,6 +73,34 @@ def _check(batch, N, C, r, dtype, seed, inplace=False):
 def test_shapes(dtype, shape):
     batch, N, C, r = shape
     _check(batch, N, C, r, dtype, seed=sum(shape))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("vectors", [512, 513, 1024, 1025, 2049])
+def test_wide_rows(dtype, vectors):
+    """Rows of 512 .. 2049 16-byte vectors: one or several copies of the row over the token block's
+    lanes, and rows taken in chunks of 1024 vectors."""
+    C = vectors * (8 if dtype == wl.BF16 else 4)
+    _check(3, 2, C, 7, dtype, seed=vectors)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_b_not_vector_aligned(dtype):
+    """B only 4-byte aligned: the forward kernel's element loads of B."""
+    _check(4, 21, 96, 30, dtype, seed=77, b_offset=1)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_empty_batch_gives_zero_gradients(dtype):
+    N, C, r = 5, 64, 9
+    A = torch.randn(N, r, device="cuda")
+    B = torch.randn(r, C, device="cuda")
+    bA, bB, bw = gu.Buf(4 * N * r, fill=0xFF), gu.Buf(4 * r * C, fill=0xFF), gu.Buf(4 * N * C, fill=0xFF)
+    s2a.lrp_bwd(0x1000, A.data_ptr(), B.data_ptr(), bA.ptr, bB.ptr, bw.ptr, 0, N, C, r, dtype,
+                torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert not bA.download(np.float32).any() and not bB.download(np.float32).any()
+    assert bA.canaries_intact() and bB.canaries_intact() and bw.canaries_intact()
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
