@@ -567,28 +567,17 @@ int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t 
     if (!x || !y || !A || !B) return S2A_ERR_NULL;
     if (!aligned(x, 16) || !aligned(y, 16) || !aligned(A, 4) || !aligned(B, 4)) return S2A_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    // a lane owns one vector position of the sample and a chunk of the batch: chunks of 8 samples
-    // (eight loads in flight, the prompt values formed once per 8) unless that leaves the chip short of lanes
     const int epv = dtype == S2A_BF16 ? 8 : 4;
     const int64_t sample = N * (C / epv);               // vectors per sample
-    const int64_t blocks = (sample + s2a::kLrpBlock - 1) / s2a::kLrpBlock;
+    const int64_t blocks = (sample + s2a::kLrpPos - 1) / s2a::kLrpPos;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
-    int64_t per = 8;
-    while (per > 2 && sample * ((batch + per - 1) / per) < 128 * 1024) per /= 2;
-    int64_t chunks = (batch + per - 1) / per;
-    if (chunks > 65535) {
-        chunks = 65535;
-        per = (batch + chunks - 1) / chunks;
-        chunks = (batch + per - 1) / per;
-    }
-    dim3 grid((unsigned)blocks, (unsigned)chunks);
     return checked_launch([&] {
         if (dtype == S2A_BF16)
-            s2a::lrp_fwd_kernel<true><<<grid, dim3(s2a::kLrpBlock), 0, st>>>(
-                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r, (int)per);
+            s2a::lrp_fwd_kernel<true><<<dim3((unsigned)blocks), dim3(s2a::kLrpFwdBlock), 0, st>>>(
+                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r);
         else
-            s2a::lrp_fwd_kernel<false><<<grid, dim3(s2a::kLrpBlock), 0, st>>>(
-                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r, (int)per);
+            s2a::lrp_fwd_kernel<false><<<dim3((unsigned)blocks), dim3(s2a::kLrpFwdBlock), 0, st>>>(
+                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r);
     });
 }
 

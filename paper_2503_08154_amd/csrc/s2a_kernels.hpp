@@ -1337,89 +1337,103 @@ __global__ __launch_bounds__(kBlock) void cap_bwd_kernel_unaligned(const void* d
 // the batch; dL/dx = dL/dy, dL/dA = dL/dy B^T, dL/dB = A^T dL/dy, both summed
 // over the batch.  Neither x nor y is needed in backward.
 //
-// Forward: the prompt is never materialised in HBM.  A lane owns one 16-byte
-// vector position of the sample (token i, channels c..c+EPV-1) and a chunk of
-// the batch: it forms its EPV prompt values P[i, c..] = sum_k A[i,k] B[k,c..]
-// once (A and B come from L2, eight rows of B in flight) and then streams x ->
-// y over its batch chunk with eight 16-byte loads in flight.  A sample holds
-// only ~150 k elements, so the batch chunks are what fills the chip.  HBM
-// traffic: x once, y once.
+// Forward: the prompt is never materialised in HBM.  A block is kLrpPos
+// neighbouring 16-byte vector positions of the sample (token i, channels
+// c..c+EPV-1) times kLrpGroups lane groups.  Group g of a position streams the
+// samples g, g+G, g+2G, ... from x to y, eight 16-byte loads in flight, so the
+// batch is what fills the chip (a sample holds only ~150 k elements).  The EPV
+// prompt values of a position, P[i, c..] = sum_k A[i,k] B[k,c..], are shared
+// work: group g adds the terms k = g, g+G, ... while its first loads of x are
+// in flight, and the G partial sums meet in LDS in fixed order -- every row of
+// B is read once per position, not once per lane.  HBM traffic: x once, y once.
 //
 // Backward: G = sum_b dL/dy[b] and dA = G B^T come from one kernel (one block
 // per token, one pass over dL/dy; G goes to a caller-provided N*C fp32
 // workspace), dB = A^T G from a second; the two products are tiny (N*C*r =
 // 4.5 MFLOP at ViT-B/16) next to the pass over dL/dy.
-constexpr int kLrpBlock = 256;
+constexpr int kLrpPos = 128;
+constexpr int kLrpGroups = 8;
+constexpr int kLrpFwdBlock = kLrpPos * kLrpGroups;
 constexpr int kLrpTokenBlock = 1024;
 constexpr int kLrpMaxRank = 64;
 
 template <bool BF16>
-__global__ __launch_bounds__(kLrpBlock) void lrp_fwd_kernel(const u32x4* x, u32x4* y,
-                                                            const float* __restrict__ A,
-                                                            const float* __restrict__ B,
-                                                            int batch, int N, int C, int r,
-                                                            int batch_chunk)
+__global__ __launch_bounds__(kLrpFwdBlock) void lrp_fwd_kernel(const u32x4* x, u32x4* y,
+                                                               const float* __restrict__ A,
+                                                               const float* __restrict__ B,
+                                                               int batch, int N, int C, int r)
 {
     constexpr int EPV = BF16 ? 8 : 4;
+    constexpr int U = 8;
+    __shared__ __align__(16) float part[kLrpGroups][kLrpPos * EPV];
+    const int pos = threadIdx.x % kLrpPos, grp = threadIdx.x / kLrpPos;
     const int vpt = C / EPV;                            // vectors per token row (the launcher checks C % EPV)
     const int64_t sample = (int64_t)N * vpt;            // vectors per sample
-    const int64_t at = (int64_t)blockIdx.x * kLrpBlock + threadIdx.x;  // this lane's vector inside a sample
-    if (at >= sample) return;
-    const int i = (int)(at / vpt), c0 = (int)(at - (int64_t)i * vpt) * EPV;
-    const int b0 = blockIdx.y * batch_chunk;
-    const int b1 = b0 + batch_chunk < batch ? b0 + batch_chunk : batch;
-    constexpr int U = 8;
-    // the first round of x is requested before the prompt values are formed: the two latencies overlap
+    const int64_t at = (int64_t)blockIdx.x * kLrpPos + pos;  // this lane's vector inside a sample
+    const bool valid = at < sample;
+    // the first round of x is requested before the prompt values are formed: the latencies overlap
     u32x4 v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (b0 + u < b1) v[u] = stream_load128(x + (b0 + u) * sample + at);
-    const float* Ai = A + (int64_t)i * r;
-    const float* Bc = B + c0;
+        if (valid && grp + u * kLrpGroups < batch) v[u] = stream_load128(x + (int64_t)(grp + u * kLrpGroups) * sample + at);
     float p[EPV];
 #pragma unroll
     for (int j = 0; j < EPV; ++j) p[j] = 0.0f;
-    constexpr int KU = 8;
-    int k = 0;
-    const bool b_vectors = ((uintptr_t)B & 15u) == 0;  // C and c0 are multiples of EPV, so rows follow B
-    for (; b_vectors && k < r; k += KU) {  // KU rows of B in flight; each sum keeps its order in k
-        u32x4 bk[KU][EPV / 4];
+    if (valid) {
+        const int i = (int)(at / vpt), c0 = (int)(at - (int64_t)i * vpt) * EPV;
+        const float* Ai = A + (int64_t)i * r;
+        const float* Bc = B + c0;
+        const bool b_vectors = ((uintptr_t)B & 15u) == 0;  // C and c0 are multiples of EPV, so rows follow B
+        constexpr int KU = kLrpMaxRank / kLrpGroups;       // all of this group's rows of B in flight
         float a[KU];
+        u32x4 bk[KU][EPV / 4];
 #pragma unroll
-        for (int u = 0; u < KU; ++u)
-            if (k + u < r) {
-                a[u] = Ai[k + u];
+        for (int q = 0; q < KU; ++q) {
+            const int k = grp + q * kLrpGroups;
+            if (k < r) {
+                a[q] = Ai[k];
 #pragma unroll
-                for (int h = 0; h < EPV / 4; ++h) bk[u][h] = *(const u32x4*)(Bc + (int64_t)(k + u) * C + 4 * h);
+                for (int h = 0; h < EPV / 4; ++h) {
+                    const float* src = Bc + (int64_t)k * C + 4 * h;
+                    if (b_vectors) bk[q][h] = *(const u32x4*)src;
+                    else bk[q][h] = u32x4{as_u32(src[0]), as_u32(src[1]), as_u32(src[2]), as_u32(src[3])};
+                }
             }
+        }
 #pragma unroll
-        for (int u = 0; u < KU; ++u)
-            if (k + u < r) {
+        for (int q = 0; q < KU; ++q)
+            if (grp + q * kLrpGroups < r) {
 #pragma unroll
-                for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a[u], as_f32(bk[u][j / 4][j % 4]), p[j]);
+                for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a[q], as_f32(bk[q][j / 4][j % 4]), p[j]);
             }
     }
-    for (; k < r; ++k) {  // B not 16-byte aligned: element loads
-        const float a = Ai[k];
 #pragma unroll
-        for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a, Bc[(int64_t)k * C + j], p[j]);
+    for (int j = 0; j < EPV; ++j) part[grp][pos * EPV + j] = p[j];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) {
+        float sum = part[0][pos * EPV + j];
+#pragma unroll
+        for (int g = 1; g < kLrpGroups; ++g) sum += part[g][pos * EPV + j];
+        p[j] = sum;
     }
-    for (int b = b0; b < b1; b += U) {
-        if (b != b0) {
+    if (!valid) return;
+    for (int b = grp; b < batch; b += U * kLrpGroups) {
+        if (b != grp) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (b + u < b1) v[u] = stream_load128(x + (b + u) * sample + at);
+                if (b + u * kLrpGroups < batch) v[u] = stream_load128(x + (int64_t)(b + u * kLrpGroups) * sample + at);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (b + u < b1) {
+            if (b + u * kLrpGroups < batch) {
                 float f[EPV];
                 unpack_vector<BF16>(v[u], f);
                 u32x4 o;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     o[j] = BF16 ? pack_bf16(f[2 * j] + p[2 * j], f[2 * j + 1] + p[2 * j + 1]) : as_u32(f[j] + p[j]);
-                stream_store128(y + (b + u) * sample + at, o);
+                stream_store128(y + (int64_t)(b + u * kLrpGroups) * sample + at, o);
             }
     }
 }
