@@ -289,6 +289,11 @@ def cpu_baseline(w: wl.Workload, target_cpu_seconds: float = 12.0):
             cpu_seconds += dt * cores
             reps += 1
     moved = 2 * bytes_per_direction(n, w.dtype) * reps
+    # the same layer once on one core (the oracle is scalar code: no threads of its own)
+    t0 = time.perf_counter()
+    _, _, packed, _ = oracle.fwd(x, w.dtype, want_near=False)
+    oracle.bwd(dy, w.dtype, packed)
+    single = time.perf_counter() - t0
     return {
         "value": round(moved / wall / 1e9, 3),
         "unit": "GB/s",
@@ -297,6 +302,8 @@ def cpu_baseline(w: wl.Workload, target_cpu_seconds: float = 12.0):
         "sample": f"one {w.name} layer ({n} elements) fwd+bwd, {reps} repetitions, "
                   f"split into {cores} contiguous chunks, one thread each",
         "elements_per_s": round(n * reps / wall, 1),
+        "single_core": {"value": round(2 * bytes_per_direction(n, w.dtype) / single / 1e9, 3), "unit": "GB/s",
+                        "elements_per_s": round(n / single, 1), "sample": "the same layer once, one thread"},
     }
 
 
