@@ -1,4 +1,4 @@
-"""The entry points under HIP graph capture: every launch goes to the caller's
+"""Every entry point under HIP graph capture: every launch goes to the caller's
 stream and nothing allocates or synchronises, so a captured forward+backward
 must replay to the bits of the eager run, every time."""
 import numpy as np
@@ -27,8 +27,22 @@ def test_forward_backward_graph_replays_match_eager():
     mask = torch.empty((n + 7) // 8, dtype=torch.uint8, device="cuda")
     qstate = torch.empty(s2a.QSTATE_FLOATS, dtype=torch.float32, device="cuda")
     sm_y = torch.empty_like(tl)
+    sm_dx = torch.empty_like(tl)
     sm_c = torch.empty(rows * ((L + 1) // 2), dtype=torch.uint8, device="cuda")
     sm_q = torch.empty(2 * rows, dtype=torch.float32, device="cuda")
+    # CAP and LRP on a [batch, N, C] view of a prefix of x
+    batch, N, C, rank, r_cap = 6, 19, 64, 30, 8
+    m = batch * N * C
+    cap_y = torch.empty(m // r_cap * 2, dtype=torch.uint8, device="cuda")
+    cap_dx = torch.empty(m * 2, dtype=torch.uint8, device="cuda")
+    lrp_y = torch.empty(m * 2, dtype=torch.uint8, device="cuda")
+    A = torch.randn(N, rank, device="cuda")
+    B = torch.randn(rank, C, device="cuda")
+    dA, dB, work = torch.empty_like(A), torch.empty_like(B), torch.empty(N, C, device="cuda")
+    out["dx_relu"] = torch.empty_like(tx)
+    out["y_silu"] = torch.empty_like(tx)
+    out["dx_silu"] = torch.empty_like(tx)
+    codes_silu = torch.empty_like(codes)
 
     def run(stream):
         s2a.act_fwd(tx.data_ptr(), out["y"].data_ptr(), codes.data_ptr(), n, w.dtype, stream)
@@ -36,15 +50,27 @@ def test_forward_backward_graph_replays_match_eager():
         s2a.act_fwd_dyn(tx.data_ptr(), out["y_dyn"].data_ptr(), codes_dyn.data_ptr(), qstate.data_ptr(), n, w.dtype, stream)
         s2a.act_bwd_dyn(tdy.data_ptr(), codes_dyn.data_ptr(), qstate.data_ptr(), out["dx_dyn"].data_ptr(), n, w.dtype, stream)
         s2a.relu_fwd(tx.data_ptr(), out["y_relu"].data_ptr(), mask.data_ptr(), n, w.dtype, stream)
+        s2a.relu_bwd(tdy.data_ptr(), mask.data_ptr(), out["dx_relu"].data_ptr(), n, w.dtype, stream)
+        s2a.silu_fwd(tx.data_ptr(), out["y_silu"].data_ptr(), codes_silu.data_ptr(), n, w.dtype, stream)
+        s2a.silu_bwd(tdy.data_ptr(), codes_silu.data_ptr(), out["dx_silu"].data_ptr(), n, w.dtype, stream)
         s2a.softmax_fwd(tl.data_ptr(), sm_y.data_ptr(), sm_c.data_ptr(), sm_q.data_ptr(), rows, L, wl.BF16, stream)
+        s2a.softmax_bwd(tl.data_ptr(), sm_c.data_ptr(), sm_q.data_ptr(), sm_dx.data_ptr(), rows, L, wl.BF16, stream)
+        s2a.cap_fwd(tx.data_ptr(), cap_y.data_ptr(), m // r_cap, r_cap, w.dtype, stream)
+        s2a.cap_bwd(cap_y.data_ptr(), cap_dx.data_ptr(), m // r_cap, r_cap, w.dtype, stream)
+        s2a.lrp_fwd(tx.data_ptr(), lrp_y.data_ptr(), A.data_ptr(), B.data_ptr(), batch, N, C, rank, w.dtype, stream)
+        s2a.lrp_bwd(tdy.data_ptr(), A.data_ptr(), B.data_ptr(), dA.data_ptr(), dB.data_ptr(), work.data_ptr(),
+                    batch, N, C, rank, w.dtype, stream)
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.cpu().numpy().copy() for t in (*out.values(), codes, codes_dyn, mask, qstate, sm_y, sm_c, sm_q)]
+        return [t.cpu().numpy().copy() for t in (*out.values(), codes, codes_dyn, codes_silu, mask, qstate, sm_y, sm_dx, sm_c, sm_q,
+                                                 cap_y, cap_dx, lrp_y, dA, dB, work)]
 
     def scrub():
-        for t in (*out.values(), codes, codes_dyn, mask, sm_y, sm_c):
+        for t in (*out.values(), codes, codes_dyn, codes_silu, mask, sm_y, sm_dx, sm_c, cap_y, cap_dx, lrp_y):
             t.fill_(0x5A)
+        for t in (dA, dB, work):
+            t.fill_(-1.0)
         qstate.fill_(-1.0)
         sm_q.fill_(-1.0)
 
