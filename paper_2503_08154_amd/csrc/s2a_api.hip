@@ -146,7 +146,7 @@ int launch_range(const void* x, float* qs, int64_t n, hipStream_t st)
     });
     if (rc != S2A_OK) return rc;
     return checked_launch([&] {
-        s2a::range_finalize_kernel<<<dim3(1), dim3(s2a::kRangeBlock), 0, st>>>(qs, (int)blocks);
+        s2a::range_finalize_kernel<<<dim3(1), dim3(s2a::kWave), 0, st>>>(qs, (int)blocks);
     });
 }
 

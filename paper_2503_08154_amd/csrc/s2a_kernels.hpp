@@ -438,27 +438,36 @@ __global__ __launch_bounds__(kRangeBlock) void range_minmax_kernel(const void* x
     }
 }
 
-// Pass 2: one block reduces the `nparts` pairs and turns (min, max) into the
+// Pass 2: one wave reduces the `nparts` pairs and turns (min, max) into the
 // scale, the binning constants and the 16 derivative levels
 // D[k] = sigma(1.702 xhat_k) + 0.22 sin(1.5 xhat_k), xhat_k = min + k * scale
 // (Eq. 9, Eq. 12), all in double, rounded once.  An empty tensor gives
-// min = max = 0.
-__global__ __launch_bounds__(kRangeBlock) void range_finalize_kernel(float* qs, int nparts)
+// min = max = 0.  A single wave: no LDS, no barrier.  The launch is all
+// latency (about 4.6 us, most of it the kernel boundary and the double
+// precision exp and sin; a 1024-lane block takes the same time).
+__global__ __launch_bounds__(kWave) void range_finalize_kernel(float* qs, int nparts)
 {
     float lo = __builtin_inff(), hi = -__builtin_inff();
-    for (int p = threadIdx.x; p < nparts; p += kRangeBlock) {
-        lo = fminf(lo, qs[kQsPartMin + p]);
-        hi = fmaxf(hi, qs[kQsPartMax + p]);
+    constexpr int PER = kRangeBlocks / kWave;  // all loads of a lane in flight together
+    float plo[PER], phi[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int p = q * kWave + (int)threadIdx.x;
+        plo[q] = p < nparts ? qs[kQsPartMin + p] : __builtin_inff();
+        phi[q] = p < nparts ? qs[kQsPartMax + p] : -__builtin_inff();
     }
-    block_minmax<kRangeBlock>(lo, hi);
-    __shared__ double range[2];
-    if (threadIdx.x == 0) {
-        const bool empty = !(lo <= hi);
-        range[0] = empty ? 0.0 : (double)lo;
-        range[1] = empty ? 0.0 : (double)hi;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        lo = fminf(lo, plo[q]);
+        hi = fmaxf(hi, phi[q]);
     }
-    __syncthreads();
-    const double dlo = range[0], dhi = range[1];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {  // butterfly: every lane ends with the result
+        lo = fminf(lo, __shfl_xor(lo, off, kWave));
+        hi = fmaxf(hi, __shfl_xor(hi, off, kWave));
+    }
+    const bool empty = !(lo <= hi);
+    const double dlo = empty ? 0.0 : (double)lo, dhi = empty ? 0.0 : (double)hi;
     const double scale = (dhi - dlo) / 15.0;
     const int k = threadIdx.x;
     if (k < 16) {
