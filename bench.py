@@ -119,8 +119,9 @@ def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds
         run_step(layers, stream, events[k], variant=variant)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in events)
-    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in events)
+    fwd_steps = [e[0].elapsed_time(e[1]) for e in events]
+    bwd_steps = [e[1].elapsed_time(e[2]) for e in events]
+    fwd_ms, bwd_ms = sum(fwd_steps), sum(bwd_steps)
     launches = steps * len(layers)
     n_total = sum(L.n for L in layers)
     bytes_dir = sum(bytes_per_direction(L.n, L.dtype) for L in layers)
@@ -134,10 +135,42 @@ def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds
         "fwd_gbs": bytes_dir * steps / (fwd_ms * 1e-3) / 1e9,
         "bwd_gbs": bytes_dir * steps / (bwd_ms * 1e-3) / 1e9,
         "bytes_per_launch": bytes_dir / len(layers),
+        # per launch, from the per-step phase times (a phase is one launch per layer)
+        "fwd_us_median": float(np.median(fwd_steps)) * 1e3 / len(layers),
+        "fwd_us_min": min(fwd_steps) * 1e3 / len(layers),
+        "bwd_us_median": float(np.median(bwd_steps)) * 1e3 / len(layers),
+        "bwd_us_min": min(bwd_steps) * 1e3 / len(layers),
     }
     del layers
     torch.cuda.empty_cache()
     return res
+
+
+def time_copy_ceiling(torch, nbytes_total: float, sets: int, steps: int, warmup: int):
+    """A plain streaming copy with the kernels' launch shape and memory instructions
+    (s2a_stream_copy) moving the same bytes per launch as an activation kernel: half in, half out."""
+    half = int(nbytes_total / 2) // 16 * 16
+    bufs = [(torch.empty(half, dtype=torch.uint8, device="cuda").fill_(0x3C),
+             torch.empty(half, dtype=torch.uint8, device="cuda")) for _ in range(sets)]
+    ptrs = [(a.data_ptr(), b.data_ptr()) for a, b in bufs]
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(warmup):
+        for a, b in ptrs:
+            s2a.stream_copy(a, b, half, stream)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for k in range(steps):
+        events[k][0].record()
+        for a, b in ptrs:
+            s2a.stream_copy(a, b, half, stream)
+        events[k][1].record()
+    torch.cuda.synchronize()
+    us = sum(e[0].elapsed_time(e[1]) for e in events) * 1e3 / (steps * sets)
+    gbs = 2 * half / us / 1e3
+    del bufs
+    torch.cuda.empty_cache()
+    return {"kernel": "s2a::stream_copy_kernel", "bytes_per_launch": 2 * half, "us_per_launch": round(us, 2),
+            "gbs": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "buffer_sets": sets}
 
 
 def time_softmax(torch, rows: int, L: int, dtype: int, sets: int, steps: int, warmup: int):
@@ -249,12 +282,16 @@ def roofline_of(res, w: wl.Workload):
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": MEASURED_TRAFFIC.get((w.name, which)),
         "us_per_launch": round(res[f"{which}_us_per_launch"], 2),
+        "us_per_launch_median": round(res[f"{which}_us_median"], 2),
+        "us_per_launch_min": round(res[f"{which}_us_min"], 2),
         "algorithmic_bytes_per_launch": res["bytes_per_launch"],
         "other_kernel": {
             "kernel": f"s2a::{'bwd' if which == 'fwd' else 'fwd'}_kernel<{dt}>",
             "achieved": round(res["bwd_gbs" if which == "fwd" else "fwd_gbs"], 1),
             "frac": round(res["bwd_gbs" if which == "fwd" else "fwd_gbs"] / HBM_PEAK_GBS, 4),
             "us_per_launch": round(res["bwd_us_per_launch" if which == "fwd" else "fwd_us_per_launch"], 2),
+            "us_per_launch_median": round(res["bwd_us_median" if which == "fwd" else "fwd_us_median"], 2),
+            "us_per_launch_min": round(res["bwd_us_min" if which == "fwd" else "fwd_us_min"], 2),
             "traffic": MEASURED_TRAFFIC.get((w.name, "bwd" if which == "fwd" else "fwd")),
         },
     }
@@ -356,6 +393,13 @@ def main():
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": roofline_of(res, w),
     }
+    # the measured ceiling of this access pattern: a math-free copy of the same bytes per launch
+    ceiling = time_copy_ceiling(torch, res["bytes_per_launch"], max(8, res["launches_per_phase"]),
+                                max(5, args.steps // 2), 3)
+    out["roofline"]["copy_ceiling"] = ceiling
+    out["roofline"]["frac_of_copy_ceiling"] = round(out["roofline"]["achieved"] / ceiling["gbs"], 4)
+    out["roofline"]["other_kernel"]["frac_of_copy_ceiling"] = round(
+        out["roofline"]["other_kernel"]["achieved"] / ceiling["gbs"], 4)
     if not args.no_targets:
         targets = {}
         for name in ("vit_l16", "vit_g14", "vit_g14_f32"):
@@ -367,7 +411,11 @@ def main():
                 tw = wl.Workload(tw.name, tw.index, tw.dtype, tw.shapes, 8, tw.dist, tw.scale, tw.dy_scale)
             r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False)
             rf = roofline_of(r, tw)
+            cc = time_copy_ceiling(torch, r["bytes_per_launch"], 8, max(5, args.steps // 2), 3)
             targets[name] = {
+                "copy_ceiling_gbs": cc["gbs"], "copy_ceiling_us": cc["us_per_launch"],
+                "fwd_frac_of_copy_ceiling": round(r["fwd_gbs"] / cc["gbs"], 4),
+                "bwd_frac_of_copy_ceiling": round(r["bwd_gbs"] / cc["gbs"], 4),
                 "fwd_gbs": round(r["fwd_gbs"], 1), "bwd_gbs": round(r["bwd_gbs"], 1),
                 "fwd_frac": round(r["fwd_gbs"] / HBM_PEAK_GBS, 4), "bwd_frac": round(r["bwd_gbs"] / HBM_PEAK_GBS, 4),
                 "fwd_us": round(r["fwd_us_per_launch"], 2), "bwd_us": round(r["bwd_us_per_launch"], 2),

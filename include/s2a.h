@@ -223,6 +223,19 @@ int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t 
 int s2a_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float* dB, float* work,
                 int64_t batch, int64_t N, int64_t C, int r, int dtype, void* stream);
 
+/*
+ * Measurement aid, not part of the method: a plain streaming copy of `nbytes`
+ * bytes (a multiple of 16; src and dst device, 16-byte aligned, not
+ * overlapping) with the same launch shape and the same load / store
+ * instructions as the activation kernels -- one 16-byte vector per lane,
+ * single-wave blocks.  The benchmark times it at the activation kernels'
+ * traffic as the measured ceiling of this access pattern (Sec. 3.2 gives no
+ * kernel design; this is what the HBM system sustains for read-once,
+ * write-once streams).  S2A_ERR_SIZE if nbytes is negative or not a multiple
+ * of 16, S2A_ERR_ALIGN for misaligned pointers.
+ */
+int s2a_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream);
+
 /* Static, NUL-terminated description of a return code.  Never NULL. */
 const char* s2a_strerror(int code);
 

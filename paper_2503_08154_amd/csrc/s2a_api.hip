@@ -612,6 +612,21 @@ int s2a_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float
     });
 }
 
+int s2a_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream)
+{
+    if (nbytes < 0 || nbytes % 16 != 0) return S2A_ERR_SIZE;
+    if (nbytes == 0) return S2A_OK;
+    if (!src || !dst) return S2A_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(dst, 16)) return S2A_ERR_ALIGN;
+    const int64_t nvec = nbytes / 16;
+    const int64_t blocks = (nvec + s2a::kWave - 1) / s2a::kWave;
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    return checked_launch([&] {
+        s2a::stream_copy_kernel<<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, (hipStream_t)stream>>>(
+            (const s2a::u32x4*)src, (s2a::u32x4*)dst, nvec);
+    });
+}
+
 const char* s2a_strerror(int code)
 {
     switch (code) {

@@ -1582,4 +1582,12 @@ __global__ __launch_bounds__(kLrpGradBBlock) void lrp_grad_b_kernel(const float*
     }
 }
 
+// ------------------------------------------------- measurement aid --------
+// The activation kernels' skeleton with the arithmetic taken out.
+__global__ __launch_bounds__(kWave) void stream_copy_kernel(const u32x4* src, u32x4* dst, int64_t nvec)
+{
+    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    if (i < nvec) stream_store128(dst + i, stream_load128(src + i));
+}
+
 }  // namespace s2a
