@@ -74,6 +74,12 @@ def test_error_paths_need_no_gpu():
     assert s2a.act_bwd_dyn(fake, fake, None, fake, 8, s2a.BF16, check=False) == s2a.ERR_NULL
     assert s2a.act_bwd_dyn(fake, fake, odd, fake, 8, s2a.BF16, check=False) == s2a.ERR_ALIGN
     assert s2a.act_bwd_dyn(None, None, fake, None, 0, s2a.BF16, check=False) == s2a.OK
+    # the measurement aid
+    assert s2a.stream_copy(fake, fake, -16, check=False) == s2a.ERR_SIZE
+    assert s2a.stream_copy(fake, fake, 24, check=False) == s2a.ERR_SIZE
+    assert s2a.stream_copy(None, fake, 32, check=False) == s2a.ERR_NULL
+    assert s2a.stream_copy(fake, odd, 32, check=False) == s2a.ERR_ALIGN
+    assert s2a.stream_copy(None, None, 0, check=False) == s2a.OK
 
 
 def test_strerror_is_total():

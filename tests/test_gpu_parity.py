@@ -253,3 +253,16 @@ def test_more_than_2_31_elements(dtype):
     parity.check_values(fetch(tdx), dx_ref, dtype, "dx", skip=diff)
     print(f"\n[n={n} dtype={dtype}] checked {pos.shape[0]} sampled elements, in-band {int(near.sum())}, "
           f"differing {int(diff.sum())}")
+
+
+@pytest.mark.parametrize("nbytes", [16, 1024, 1040, 16 * 64 * 37 + 16, 1 << 24])
+def test_stream_copy_is_a_copy(nbytes):
+    """The measurement aid moves the bytes it is given and nothing else."""
+    g = np.random.Generator(np.random.Philox(nbytes))
+    src = g.integers(0, 256, nbytes, dtype=np.uint8)
+    bs = gu.Buf(nbytes).upload(src)
+    bd = gu.Buf(nbytes, fill=0x11)
+    s2a.stream_copy(bs.ptr, bd.ptr, nbytes, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert bd.canaries_intact() and bs.canaries_intact()
+    np.testing.assert_array_equal(bd.download(np.uint8), src)
