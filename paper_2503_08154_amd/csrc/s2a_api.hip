@@ -199,13 +199,36 @@ int softmax_group(int64_t L)
 // bf16 runs fastest with 8 lanes x 13 pairs, fp32 with 16 lanes x 7 pairs.
 template <bool BF16>
 constexpr int pair_slots() { return BF16 ? 16 : 8; }
+// How many rows of one wave meet in the same LDS bank (64 banks of 4 bytes) when every lane
+// reads one pair: row r of the wave starts r * row_bytes into the span and its G lanes cover
+// G * pair_bytes from there.
+int lds_row_conflicts(int64_t row_bytes, int g, int pair_bytes)
+{
+    int hits[64] = {0};
+    int worst = 0;
+    for (int r = 0; r < 64 / g; ++r) {
+        const int64_t a = r * row_bytes, b = a + (int64_t)g * pair_bytes - 1;
+        for (int64_t w = a / 4; w <= b / 4; ++w)
+            if (++hits[w % 64] > worst) worst = hits[w % 64];
+    }
+    return worst;
+}
 template <bool BF16>
 int softmax_pair_group(int64_t L)
 {
     const int64_t pairs = (L + 1) / 2;
-    for (int g = 4; g <= 64; g *= 2)
-        if ((pairs + g - 1) / g <= pair_slots<BF16>()) return g;
-    return 0;
+    const int es = BF16 ? 2 : 4, gmax = BF16 ? 32 : 64;
+    int g = 4;
+    while (g <= gmax && (pairs + g - 1) / g > pair_slots<BF16>()) g *= 2;
+    if (g > gmax) return 0;
+    // rows whose length puts more than four rows of a wave on the same banks (powers of two and
+    // their neighbours) take a group twice as wide, i.e. half the rows per wave.  Measured, bf16:
+    // L = 64: 31 -> 25 us for 118 MB; L = 128: 48 -> 33 us for 175 MB; L = 256: 34 -> 31.5 us;
+    // a second doubling loses more in per-wave work than it gains.
+    if (2 * g <= gmax && lds_row_conflicts(L * es, g, 2 * es) > 4 &&
+        lds_row_conflicts(L * es, 2 * g, 2 * es) < lds_row_conflicts(L * es, g, 2 * es))
+        g *= 2;
+    return g;
 }
 
 // Row groups per block of the staged kernels, by measurement at the ViT-B/16
@@ -227,13 +250,12 @@ void softmax_lds(int L, int passes, int* data_bytes, int* total_bytes)
     *total_bytes = *data_bytes + ((rpb * ((L + 1) / 2) + 15 + 15) / 16) * 16;
 }
 
-// Calls f(std::integral_constant<int, SLOTS>) for SLOTS == slots.  Groups wider
-// than 4 lanes only occur for rows that need more than half the slots.
+// Calls f(std::integral_constant<int, SLOTS>) for SLOTS == slots.
 template <int G, int MAXS, int S = MAXS, typename F>
 void with_slots(int slots, F f)
 {
     if (slots == S) f(std::integral_constant<int, S>{});
-    else if constexpr (S > (G == 4 ? 1 : MAXS / 2 + 1)) with_slots<G, MAXS, S - 1>(slots, f);
+    else if constexpr (S > 1) with_slots<G, MAXS, S - 1>(slots, f);
 }
 
 template <bool BF16, int G>
