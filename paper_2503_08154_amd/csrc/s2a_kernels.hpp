@@ -321,8 +321,15 @@ __global__ __launch_bounds__(kWave) void fwd_kernel(const u32x4* x, u32x4* y,
     if constexpr (DYN) bin = BinRange{qs[kQsInv], qs[kQsOff]};
     const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
     if (i < nvec) {
+        // A wave that is about to issue its load or its stores goes ahead of the waves that are
+        // in their arithmetic: the memory system is the bottleneck, so its requests should never
+        // wait for an issue slot.  Measured: fp32 forward 87.1 -> 85.5 us at the ViT-G shape
+        // (82.2 -> 83.7 % of peak); no change for bf16, whose arithmetic is lighter.
+        __builtin_amdgcn_s_setprio(3);
         u32x4 v = stream_load128(x + i);
+        __builtin_amdgcn_s_setprio(0);
         uint32_t c = fwd_vector<BF16, ACT>(v, bin);
+        __builtin_amdgcn_s_setprio(3);
         stream_store128(y + i, v);
         store_codes<BF16>(codes, i, c);
     } else if (i == nvec) {  // one lane finishes the n % EPV leftover elements
