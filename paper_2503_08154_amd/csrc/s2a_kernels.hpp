@@ -9,11 +9,13 @@
 //   backward  dx = dy * D[code],  D[k] = Eq. 12 at the k-th representative (Eq. 9)
 //
 // The path is bound by HBM bandwidth (2e + 0.5 bytes per element and
-// direction, e = element size), so the design is: one 128-bit load per lane
-// and step, laid out so that a wavefront touches contiguous kilobytes; all
-// packing done in registers; several independent loads in flight per lane;
-// no LDS on the vector path (the 64-byte derivative table of the backward pass
-// lives in one register per lane and is read with a cross-lane permute).
+// direction, e = element size), so the design is: one 128-bit load per lane,
+// laid out so that a wavefront touches contiguous kilobytes; all packing done
+// in registers; no LDS on the vector path (the 64-byte derivative table of the
+// backward pass lives in one register per lane and is read with a cross-lane
+// permute).  Further down, with the same skeleton where it applies: the
+// measured-range quantizer, SiLU, the ReLU bit mask, softmax with 4-bit saved
+// output, Channel Average Pooling and the Low-Rank Prompt.
 //
 // Work unit: a "vector" = 16 bytes of x (8 bf16 or 4 fp32).  Vector v owns
 // elements [v*EPV, (v+1)*EPV) and code bytes [v*EPV/2, (v+1)*EPV/2), so no
