@@ -201,7 +201,11 @@ __device__ __forceinline__ uint32_t stream_load16(const uint16_t* p) { return __
 
 __device__ __forceinline__ void stream_store128(u32x4* p, u32x4 v)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" ::"v"(p), "v"(v) : "memory");
+    // s_nop 1: a store of more than 64 bits reads its data registers for up to two more wait
+    // states, and a VALU write to one of them in that window corrupts the stored value.  The
+    // compiler inserts the wait for stores it emits itself, but it cannot see into this string
+    // (seen as a few garbage elements per some launches of a loop that refills the registers).
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void stream_store32(uint32_t* p, uint32_t v)
 {
@@ -752,10 +756,25 @@ __device__ __forceinline__ T group_reduce(T v, F f)
     if (G >= 64) v = f(v, __shfl_xor(v, 32, kWave));
     return v;
 }
+// A DPP operand must not be read within two wait states of the VALU write that produced it.
+// The compiler spaces the instructions it emits itself, but it does not look into asm strings,
+// so a value that comes out of vmax / vmin / vmax3 / vmin3 passes through this before a
+// cross-lane move reads it: the asm both waits and is the value's last definition.
+__device__ __forceinline__ float settled(float v)
+{
+    asm("s_nop 1" : "+v"(v));
+    return v;
+}
 template <int G>
-__device__ __forceinline__ float group_max(float v) { return group_reduce<G>(v, [](float a, float b) { return vmax(a, b); }); }
+__device__ __forceinline__ float group_max(float v)
+{
+    return group_reduce<G>(settled(v), [](float a, float b) { return settled(vmax(a, b)); });
+}
 template <int G>
-__device__ __forceinline__ float group_min(float v) { return group_reduce<G>(v, [](float a, float b) { return vmin(a, b); }); }
+__device__ __forceinline__ float group_min(float v)
+{
+    return group_reduce<G>(settled(v), [](float a, float b) { return settled(vmin(a, b)); });
+}
 template <int G, typename T>
 __device__ __forceinline__ T group_sum(T v) { return group_reduce<G>(v, [](T a, T b) { return a + b; }); }
 

@@ -48,7 +48,20 @@ def _check(batch, N, C, r, dtype, seed, inplace=False, b_offset=0):
     tol = 1e-6 * (np.abs(wl.storage_to_f64(x, dtype)).reshape(batch, N, C) + mag[None]).reshape(-1)
     if dtype == wl.BF16:
         tol = tol + parity.bf16_ulp(y_ref)
-    assert (np.abs(y - y_ref) <= tol).all(), f"y: worst {np.max(np.abs(y - y_ref) / tol):.2f}x the tolerance"
+    bad = ~(np.abs(y - y_ref) <= tol)
+    if bad.any():
+        b, i, c = np.nonzero(bad.reshape(batch, N, C))
+        x_ok = inplace or bool((bx.download(gu.storage_np(dtype)).view(np.uint8) == x.view(np.uint8)).all())
+        by2 = gu.Buf(n * es, fill=0xFF)   # the same launch once more, for the failure report only
+        if not inplace:
+            s2a.lrp_fwd(bx.ptr, by2.ptr, tA.data_ptr(), tB.data_ptr(), batch, N, C, r, dtype, st)
+        again = int((~(np.abs(wl.storage_to_f64(by2.download(gu.storage_np(dtype)), dtype) - y_ref) <= tol)).sum())
+        raise AssertionError(
+            f"[x on the device intact: {x_ok}; a second launch leaves {again} elements out] "
+            f"y: {int(bad.sum())} elements out, worst {np.nanmax(np.abs(y - y_ref) / tol):.2f}x the tolerance; "
+            f"samples {np.unique(b)[:12]}, tokens {np.unique(i)[:12]}, channels {np.unique(c)[:24]} "
+            f"({len(np.unique(b))} samples, {len(np.unique(i))} tokens, {len(np.unique(c))} channels); "
+            f"first: y[{b[0]},{i[0]},{c[0]}] = {y.reshape(batch, N, C)[b[0], i[0], c[0]]!r} vs {y_ref.reshape(batch, N, C)[b[0], i[0], c[0]]!r}")
 
     bdy = gu.Buf(n * es).upload(dy)
     bA = gu.Buf(4 * N * r, fill=0xFF)
@@ -82,6 +95,12 @@ def test_wide_rows(dtype, vectors):
     lanes, and rows taken in chunks of 1024 vectors."""
     C = vectors * (8 if dtype == wl.BF16 else 4)
     _check(3, 2, C, 7, dtype, seed=vectors)
+
+
+def test_swin_stage_shape():
+    """Many tokens, few channels ([16, 3136, 128], the first Swin-B stage): 64 copies of a token's
+    channel vectors per block in the backward kernel."""
+    _check(16, 3136, 128, 30, wl.BF16, seed=3136)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
