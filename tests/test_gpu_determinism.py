@@ -1,0 +1,97 @@
+"""Every entry point, launched several times on the same inputs at a full-size shape, must write the
+same bytes every time: no kernel depends on the order or the timing in which its waves run.
+(An intermittent register hazard once showed up exactly like this: a few garbage elements in one
+launch out of four.)"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_08154_amd import s2a
+from paper_2503_08154_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+REPEATS = 6
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
+
+
+def _same(outs, what):
+    torch.cuda.synchronize()
+    first = [t.clone() for t in outs[0]]
+    for k, o in enumerate(outs[1:], 1):
+        for a, b in zip(first, o):
+            assert torch.equal(a, b), f"{what}: launch {k} differs from launch 0 in {int((a != b).sum())} bytes"
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_activation_kernels(dtype):
+    s2a.qtable_init(16)
+    w = wl.WORKLOADS["vit_b16"]
+    n = w.sizes()[0] // 2 + 3
+    x = wl.draw_x(n, "normal", 1.5, dtype, seed=1)
+    dy = wl.draw_dy(n, 1e-2, dtype, seed=2)
+    tx, tdy = _dev(x), _dev(dy)
+    st = torch.cuda.current_stream().cuda_stream
+    outs = []
+    for _ in range(REPEATS):
+        y, dx, y2, dx2, y3, dx3, y4 = (torch.empty_like(tx) for _ in range(7))
+        c, c2, c3 = (torch.empty((n + 1) // 2, dtype=torch.uint8, device="cuda") for _ in range(3))
+        m = torch.empty((n + 7) // 8, dtype=torch.uint8, device="cuda")
+        q = torch.zeros(s2a.QSTATE_FLOATS, dtype=torch.float32, device="cuda")
+        s2a.act_fwd(tx.data_ptr(), y.data_ptr(), c.data_ptr(), n, dtype, st)
+        s2a.act_bwd(tdy.data_ptr(), c.data_ptr(), dx.data_ptr(), n, dtype, st)
+        s2a.act_fwd_dyn(tx.data_ptr(), y2.data_ptr(), c2.data_ptr(), q.data_ptr(), n, dtype, st)
+        s2a.act_bwd_dyn(tdy.data_ptr(), c2.data_ptr(), q.data_ptr(), dx2.data_ptr(), n, dtype, st)
+        s2a.silu_fwd(tx.data_ptr(), y3.data_ptr(), c3.data_ptr(), n, dtype, st)
+        s2a.silu_bwd(tdy.data_ptr(), c3.data_ptr(), dx3.data_ptr(), n, dtype, st)
+        s2a.relu_fwd(tx.data_ptr(), y4.data_ptr(), m.data_ptr(), n, dtype, st)
+        outs.append((y, dx, y2, dx2, y3, dx3, y4, c, c2, c3, m, q.view(torch.uint8)))
+    _same(outs, "activation kernels")
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("L", [49, 128, 197, 257])
+def test_softmax(dtype, L):
+    rows = (64 * 12 * 197 * 197) // (4 * L)
+    x = wl.draw_x(rows * L, "normal", 2.0, dtype, seed=L)
+    dy = wl.draw_dy(rows * L, 1e-2, dtype, seed=L + 1)
+    tx, tdy = _dev(x), _dev(dy)
+    st = torch.cuda.current_stream().cuda_stream
+    outs = []
+    for _ in range(REPEATS):
+        y, dx = torch.empty_like(tx), torch.empty_like(tx)
+        c = torch.empty(rows * ((L + 1) // 2), dtype=torch.uint8, device="cuda")
+        q = torch.empty(2 * rows, dtype=torch.float32, device="cuda")
+        s2a.softmax_fwd(tx.data_ptr(), y.data_ptr(), c.data_ptr(), q.data_ptr(), rows, L, dtype, st)
+        s2a.softmax_bwd(tdy.data_ptr(), c.data_ptr(), q.data_ptr(), dx.data_ptr(), rows, L, dtype, st)
+        outs.append((y, dx, c, q.view(torch.uint8)))
+    _same(outs, f"softmax L={L}")
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("shape", [(64, 197, 768), (16, 3136, 128), (8, 49, 1024)])
+def test_cap_and_lrp(dtype, shape):
+    batch, N, C = shape
+    rank, r_cap = 30, 8
+    n = batch * N * C
+    x = wl.draw_x(n, "normal", 1.5, dtype, seed=N)
+    tx = _dev(x)
+    A = torch.randn(N, rank, device="cuda") * 0.3
+    B = torch.randn(rank, C, device="cuda") * 0.3
+    es = 4 if dtype == wl.F32 else 2
+    st = torch.cuda.current_stream().cuda_stream
+    outs = []
+    for _ in range(REPEATS):
+        y = torch.empty_like(tx)
+        cy = torch.empty(n // r_cap * es, dtype=torch.uint8, device="cuda")
+        cdx = torch.empty_like(tx)
+        dA, dB, work = torch.empty_like(A), torch.empty_like(B), torch.empty(N, C, device="cuda")
+        s2a.lrp_fwd(tx.data_ptr(), y.data_ptr(), A.data_ptr(), B.data_ptr(), batch, N, C, rank, dtype, st)
+        s2a.lrp_bwd(tx.data_ptr(), A.data_ptr(), B.data_ptr(), dA.data_ptr(), dB.data_ptr(), work.data_ptr(),
+                    batch, N, C, rank, dtype, st)
+        s2a.cap_fwd(tx.data_ptr(), cy.data_ptr(), n // r_cap, r_cap, dtype, st)
+        s2a.cap_bwd(cy.data_ptr(), cdx.data_ptr(), n // r_cap, r_cap, dtype, st)
+        outs.append((y, cy, cdx, dA.view(torch.uint8), dB.view(torch.uint8), work.view(torch.uint8)))
+    _same(outs, f"cap / lrp {shape}")
