@@ -402,13 +402,14 @@ def main():
         out["roofline"]["other_kernel"]["achieved"] / ceiling["gbs"], 4)
     if not args.no_targets:
         targets = {}
-        for name in ("vit_l16", "vit_g14", "vit_g14_f32"):
+        for name in ("vit_l16", "swin_b", "vit_g14", "vit_g14_f32"):
             if name == w.name:
                 continue
             tw = wl.WORKLOADS[name]
             # single-launch workloads get 8 buffer sets so that every launch reads cold HBM
             if tw.layers == 1:
-                tw = wl.Workload(tw.name, tw.index, tw.dtype, tw.shapes, 8, tw.dist, tw.scale, tw.dy_scale)
+                sets = 8 if len(tw.shapes) == 1 else 3     # swin_b: 4 stages x 3 sets, 2.6 GB per direction
+                tw = wl.Workload(tw.name, tw.index, tw.dtype, tw.shapes, sets, tw.dist, tw.scale, tw.dy_scale)
             r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False)
             rf = roofline_of(r, tw)
             cc = time_copy_ceiling(torch, r["bytes_per_launch"], 8, max(5, args.steps // 2), 3)
