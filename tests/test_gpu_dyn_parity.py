@@ -36,11 +36,11 @@ def _draw(n, kind, dtype, seed):
     return wl.to_storage(a, dtype)
 
 
-def _run_dyn(x, dy, dtype, offset_elems=0, code_offset=0, packed_for_bwd=None):
+def _run_dyn(x, dy, dtype, offset_elems=0, code_offset=0, packed_for_bwd=None, inplace=False):
     n = x.shape[0]
     es = gu.esize(dtype)
     bx = gu.Buf(n * es, offset_elems * es).upload(x)
-    by = gu.Buf(n * es, offset_elems * es)
+    by = bx if inplace else gu.Buf(n * es, offset_elems * es)
     bc = gu.Buf((n + 1) // 2, code_offset)
     bq = gu.Buf(4 * s2a.QSTATE_FLOATS)
     st = torch.cuda.current_stream().cuda_stream
@@ -50,10 +50,10 @@ def _run_dyn(x, dy, dtype, offset_elems=0, code_offset=0, packed_for_bwd=None):
     y = by.download(gu.storage_np(dtype))
     packed = bc.download(np.uint8)
     qs = bq.download(np.float32)
-    bdy = gu.Buf(n * es, offset_elems * es).upload(dy)
-    bdx = gu.Buf(n * es, offset_elems * es)
     outs = []
     for pk in ([packed] if packed_for_bwd is None else [packed, packed_for_bwd]):
+        bdy = gu.Buf(n * es, offset_elems * es).upload(dy)
+        bdx = bdy if inplace else gu.Buf(n * es, offset_elems * es)
         bc2 = gu.Buf((n + 1) // 2, code_offset).upload(pk)
         s2a.act_bwd_dyn(bdy.ptr, bc2.ptr, bq.ptr, bdx.ptr, n, dtype, st)
         torch.cuda.synchronize()
@@ -87,6 +87,16 @@ def test_sizes_and_ranges(dtype, kind, n):
     x = _draw(n, kind, dtype, seed=100 + n)
     dy = wl.draw_dy(n, 1.0, dtype, seed=200 + n)
     _check(x, dy, dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("off", [0, 1])
+def test_in_place(dtype, off):
+    """y over x (the range pass reads x before the forward kernel overwrites it) and dx over dy."""
+    n = 8192 * 7 + 5
+    x = _draw(n, "small", dtype, seed=17)
+    dy = wl.draw_dy(n, 1.0, dtype, seed=18)
+    _check(x, dy, dtype, offset_elems=off, inplace=True)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)

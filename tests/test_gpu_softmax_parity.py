@@ -174,3 +174,35 @@ def test_vit_b16_attention_full_size(dtype):
     dy = wl.draw_dy(rows * L, 1e-2, dtype, seed=2025)
     near, differing = _run_and_check(x, dy, dtype, rows, L)
     print(f"\n[softmax vit_b16 attention dtype={dtype}] n={rows * L} in-band={near} differing={differing}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("L", [49, 128, 197, 513])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_in_place(dtype, L, offset):
+    """y written over x and dx over dy (several blocks; the staged and the element-wise kernels)."""
+    rows = 301
+    n, rb, es = rows * L, (L + 1) // 2, gu.esize(dtype)
+    x = _logits(rows, L, dtype, seed=900 + L)
+    dy = wl.draw_dy(n, 1.0, dtype, seed=901 + L)
+    st = torch.cuda.current_stream().cuda_stream
+    y_ref, code_ref, packed_ref, qmin, qscale, near = oracle.softmax_fwd(x, dtype, rows, L, band_t=BAND_T[dtype])
+    bx = gu.Buf(n * es, offset * es).upload(x)
+    bc = gu.Buf(rows * rb, offset, fill=0xFF)
+    bq = gu.Buf(8 * rows, fill=0xFF)
+    s2a.softmax_fwd(bx.ptr, bx.ptr, bc.ptr, bq.ptr, rows, L, dtype, st)
+    torch.cuda.synchronize()
+    assert bx.canaries_intact() and bc.canaries_intact()
+    parity.check_values(bx.download(gu.storage_np(dtype)), y_ref, dtype, "y")
+    got = np.stack([parity.unpack(bc.download(np.uint8)[r * rb:(r + 1) * rb], L) for r in range(rows)]).reshape(-1)
+    assert not ((got != code_ref) & (near == 0)).any()
+    qp32 = np.stack([qmin, qscale], axis=1).astype(np.float32)
+    dx_ref = oracle.softmax_bwd(dy, dtype, packed_ref, qp32[:, 0].astype(np.float64), qp32[:, 1].astype(np.float64), rows, L)
+    yh = code_ref * np.repeat(qp32[:, 1].astype(np.float64), L) + np.repeat(qp32[:, 0].astype(np.float64), L)
+    bdy = gu.Buf(n * es, offset * es).upload(dy)
+    bc2 = gu.Buf(rows * rb, offset).upload(packed_ref)
+    bq2 = gu.Buf(8 * rows).upload(qp32.reshape(-1))
+    s2a.softmax_bwd(bdy.ptr, bc2.ptr, bq2.ptr, bdy.ptr, rows, L, dtype, st)
+    torch.cuda.synchronize()
+    assert bdy.canaries_intact()
+    _check_dx(bdy.download(gu.storage_np(dtype)), dx_ref, dtype, _dx_scale(yh, wl.storage_to_f64(dy, dtype), rows, L))
