@@ -206,3 +206,48 @@ def test_in_place(dtype, L, offset):
     torch.cuda.synchronize()
     assert bdy.canaries_intact()
     _check_dx(bdy.download(gu.storage_np(dtype)), dx_ref, dtype, _dx_scale(yh, wl.storage_to_f64(dy, dtype), rows, L))
+
+
+def test_more_than_2_31_bytes():
+    """A bf16 tensor whose byte offsets pass 2^31 (5.45 M rows of 197): row groups at the start, across
+    the 2^31-byte mark and at the end are compared with the oracle; forward and backward."""
+    L, dtype = 197, wl.BF16
+    rb = (L + 1) // 2
+    block_rows = 1 << 16
+    block = _logits(block_rows, L, dtype, seed=31)
+    rows = (1 << 31) // (L * 2) + 1534
+    reps = -(-rows // block_rows)
+    x = np.tile(block, reps)[:rows * L]
+    dyb = wl.draw_dy(block_rows * L, 1e-2, dtype, seed=32)
+    tx = torch.from_numpy(x.view(np.uint8)).cuda()
+    ty = torch.empty_like(tx)
+    tc = torch.empty(rows * rb, dtype=torch.uint8, device="cuda")
+    tq = torch.empty(2 * rows, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    s2a.softmax_fwd(tx.data_ptr(), ty.data_ptr(), tc.data_ptr(), tq.data_ptr(), rows, L, dtype, st)
+    tdy = torch.from_numpy(np.tile(dyb, reps)[:rows * L].view(np.uint8)).cuda()
+    del tx
+    tdx = torch.empty_like(tdy)
+    s2a.softmax_bwd(tdy.data_ptr(), tc.data_ptr(), tq.data_ptr(), tdx.data_ptr(), rows, L, dtype, st)
+    torch.cuda.synchronize()
+    mark = (1 << 31) // (L * 2)
+    for r0 in (0, mark - 700, rows - 1400):
+        nr = 1400
+        xs = x[r0 * L:(r0 + nr) * L]
+        y_ref, code_ref, packed_ref, qmin, qscale, near = oracle.softmax_fwd(xs, dtype, nr, L, band_t=BAND_T[dtype])
+        y = ty[r0 * L * 2:(r0 + nr) * L * 2].cpu().numpy().view(np.uint16)
+        parity.check_values(y, y_ref, dtype, "y")
+        packed = tc[r0 * rb:(r0 + nr) * rb].cpu().numpy()
+        got = np.stack([parity.unpack(packed[r * rb:(r + 1) * rb], L) for r in range(nr)]).reshape(-1)
+        diff = got != code_ref
+        assert not (diff & (near == 0)).any(), f"rows from {r0}: a code differs outside the band"
+        qp = tq[2 * r0:2 * (r0 + nr)].cpu().numpy().reshape(nr, 2)
+        np.testing.assert_allclose(qp[:, 0], qmin, rtol=QP_RTOL[dtype], atol=1e-37)
+        # backward on the GPU's own codes and parameters; rows with a legitimately differing code are skipped
+        k0 = (r0 * L) % (block_rows * L)            # the gradients repeat with the block, like x
+        dys = np.concatenate([dyb, dyb])[k0:k0 + nr * L]
+        dx_ref = oracle.softmax_bwd(dys, dtype, packed_ref, qmin, qscale, nr, L)
+        yh = code_ref * np.repeat(qscale, L) + np.repeat(qmin, L)
+        dx = tdx[r0 * L * 2:(r0 + nr) * L * 2].cpu().numpy().view(np.uint16)
+        _check_dx(dx, dx_ref, dtype, _dx_scale(yh, wl.storage_to_f64(dys, dtype), nr, L), factor=10.0,
+                  skip_rows=diff.reshape(nr, L).any(axis=1), rows=nr, L=L)
