@@ -71,3 +71,34 @@ def test_argument_errors():
     assert s2a.cap_bwd(fake, fake, 8, 8, 5, check=False) == s2a.ERR_DTYPE
     assert s2a.cap_bwd(None, fake, 8, 8, s2a.BF16, check=False) == s2a.ERR_NULL
     assert s2a.cap_fwd(None, None, 0, 8, s2a.BF16, check=False) == s2a.OK
+
+
+def test_more_than_2_31_elements():
+    """bf16 input just above 2^31 elements, r = 8: spans of outputs at both ends, across the mark and
+    at random places against the oracle; the backward pass over the same sizes, exactly."""
+    dtype, r = wl.BF16, 8
+    tile_n = 1 << 22
+    n_in = (1 << 31) + 8 * 640
+    n_out = n_in // r
+    tile_x = wl.draw_x(tile_n, "normal", 1.0, dtype, seed=616)
+    tx = torch.from_numpy(tile_x.view(np.int16)).cuda().repeat(-(-n_in // tile_n))[:n_in]
+    ty = torch.empty(n_out, dtype=torch.int16, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    s2a.cap_fwd(tx.data_ptr(), ty.data_ptr(), n_out, r, dtype, st)
+    torch.cuda.synchronize()
+    g = np.random.default_rng(6)
+    spans = [(0, 2048), (n_out - 2048, 2048), ((1 << 31) // r - 1024, 1024 + 640)] + [(int(a), 2048) for a in g.integers(0, n_out - 2048, 29)]
+    for a, m in spans:
+        pos = np.arange(a * r, (a + m) * r, dtype=np.int64) % tile_n
+        xs = tile_x[pos].copy()
+        y_ref = oracle.cap_fwd(xs, dtype, r)
+        tol = 1e-6 * np.abs(wl.storage_to_f64(xs, dtype)).reshape(m, r).mean(axis=1) + parity.bf16_ulp(y_ref)
+        got = wl.storage_to_f64(ty[a:a + m].cpu().numpy().view(np.uint16), dtype)
+        assert (np.abs(got - y_ref) <= tol).all(), f"outputs from {a}"
+    # backward: dy = the forward's y, dx over the input buffer
+    s2a.cap_bwd(ty.data_ptr(), tx.data_ptr(), n_out, r, dtype, st)
+    torch.cuda.synchronize()
+    for a, m in spans:
+        dys = ty[a:a + m].cpu().numpy().view(np.uint16)
+        np.testing.assert_array_equal(wl.storage_to_f64(tx[a * r:(a + m) * r].cpu().numpy().view(np.uint16), dtype),
+                                      oracle.cap_bwd(dys, dtype, r))

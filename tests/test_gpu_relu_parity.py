@@ -99,3 +99,35 @@ def test_workload_full_size(name):
     np.testing.assert_array_equal(wl.storage_to_f64(ty.cpu().numpy().view(gu.storage_np(w.dtype)), w.dtype), y_ref)
     np.testing.assert_array_equal(wl.storage_to_f64(tdx.cpu().numpy().view(gu.storage_np(w.dtype)), w.dtype),
                                   oracle.relu_bwd(dy, w.dtype, packed))
+
+
+def test_more_than_2_31_elements():
+    """bf16, n just above 2^31 with a ragged tail: a seeded tile repeated on the device; spans at both
+    ends, across the 2^31 mark and at random places are compared bit for bit with the oracle."""
+    dtype = wl.BF16
+    tile_n = (1 << 22) + 8                      # a multiple of 8: spans that start on a tile boundary own whole mask bytes
+    n = (1 << 31) + 8 * 64 * 3 + 5
+    tile_x = wl.draw_x(tile_n, "normal", 1.0, dtype, seed=515)
+    tile_dy = wl.draw_dy(tile_n, 1.0, dtype, seed=516)
+    reps = -(-n // tile_n)
+    tx = torch.from_numpy(tile_x.view(np.int16)).cuda().repeat(reps)[:n]
+    ty = torch.empty_like(tx)
+    tm = torch.empty((n + 7) // 8, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    s2a.relu_fwd(tx.data_ptr(), ty.data_ptr(), tm.data_ptr(), n, dtype, st)
+    torch.cuda.synchronize()
+    del tx
+    tdy = torch.from_numpy(tile_dy.view(np.int16)).cuda().repeat(reps)[:n]
+    tdx = torch.empty_like(tdy)
+    s2a.relu_bwd(tdy.data_ptr(), tm.data_ptr(), tdx.data_ptr(), n, dtype, st)
+    torch.cuda.synchronize()
+    g = np.random.default_rng(5)
+    spans = [(0, 4096), ((n - 5000) & ~7, n - ((n - 5000) & ~7)), ((1 << 31) - 2048, 3072)]
+    spans += [(int(a) & ~7, 4096) for a in g.integers(0, n - 4096, 61)]
+    for a, m in spans:
+        pos = np.arange(a, a + m, dtype=np.int64) % tile_n
+        y_ref, _, packed = oracle.relu_fwd(tile_x[pos].copy(), dtype)
+        dx_ref = oracle.relu_bwd(tile_dy[pos].copy(), dtype, packed)
+        np.testing.assert_array_equal(tm[a // 8:(a + m + 7) // 8].cpu().numpy(), packed)
+        np.testing.assert_array_equal(wl.storage_to_f64(ty[a:a + m].cpu().numpy().view(np.uint16), dtype), y_ref)
+        np.testing.assert_array_equal(wl.storage_to_f64(tdx[a:a + m].cpu().numpy().view(np.uint16), dtype), dx_ref)
