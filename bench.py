@@ -39,10 +39,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 # known size).  Measured offline; the summaries are under profiles/.  None = not measured.
 MEASURED_TRAFFIC = {
     # (workload, kernel): bytes per launch -- profiles/fwd_bwd_kernels_hbm_traffic_pmc.txt
-    ("vit_b16", "fwd"): 174292256, ("vit_b16", "bwd"): 174287059,
-    ("vit_l16", "fwd"): 232384067, ("vit_l16", "bwd"): 232382979,
-    ("vit_g14", "fwd"): 303167841, ("vit_g14", "bwd"): 303163114,
-    ("vit_g14_f32", "fwd"): 572655648, ("vit_g14_f32", "bwd"): 572650524,
+    ("vit_b16", "fwd"): 174260056, ("vit_b16", "bwd"): 174263174,
+    ("vit_l16", "fwd"): 232370185, ("vit_l16", "bwd"): 232369801,
+    ("vit_g14", "fwd"): 303152134, ("vit_g14", "bwd"): 303148119,
+    ("vit_g14_f32", "fwd"): 572653184, ("vit_g14_f32", "bwd"): 572650049,
 }
 
 

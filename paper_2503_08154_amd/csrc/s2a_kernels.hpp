@@ -188,13 +188,17 @@ __device__ __forceinline__ void store_elem(void* p, int64_t i, float v)
 template <bool BF16, int ACT>
 __device__ __forceinline__ float gelu(float x) { return BF16 ? gelu_fast<ACT>(x) : gelu_accurate<ACT>(x); }
 
-// Streaming memory access.  Loads carry the non-temporal hint (nt).  Stores
-// carry "sc0 sc1 nt": written through to memory at system scope and not kept
-// in L2 or the on-die cache -- the outputs are not read again by this kernel,
-// and on MI355X a copy kernel with these stores runs 4 % faster than with nt
-// alone (80 % vs 77 % of the HBM peak at 100 MB).  The compiler offers no
-// source-level spelling for that combination without also serialising the
-// stores, so the three store instructions are written out.
+// Streaming memory access.  Loads carry the non-temporal hint (nt).  The
+// 16-byte stores carry "sc0 sc1 nt": written through to memory at system scope
+// and not kept in L2 or the on-die cache -- the outputs are not read again by
+// this kernel, and on MI355X a copy kernel with these stores runs 4 % faster
+// than with nt alone (80 % vs 77 % of the HBM peak at 100 MB).  The small
+// stores of the packed codes (4 or 2 bytes per lane) carry "sc1" only: written
+// through at device scope but without the streaming hint.  With nt on them the
+// forward kernels ran 3-5 % slower (ViT-L bf16 80.3 -> 83.3 % of peak, ViT-G
+// fp32 83.3 -> 87.7 %); plain write-back stores come out between the two.  The
+// compiler offers no source-level spelling for these combinations without also
+// serialising the stores, so the store instructions are written out.
 __device__ __forceinline__ u32x4 stream_load128(const u32x4* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ uint32_t stream_load32(const uint32_t* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ uint32_t stream_load16(const uint16_t* p) { return __builtin_nontemporal_load(p); }
@@ -209,11 +213,11 @@ __device__ __forceinline__ void stream_store128(u32x4* p, u32x4 v)
 }
 __device__ __forceinline__ void stream_store32(uint32_t* p, uint32_t v)
 {
-    asm volatile("global_store_dword %0, %1, off sc0 sc1 nt" ::"v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void stream_store16(uint16_t* p, uint32_t v)
 {
-    asm volatile("global_store_short %0, %1, off sc0 sc1 nt" ::"v"(p), "v"(v) : "memory");
+    asm volatile("global_store_short %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
 
 // The packed codes of one vector: a dword (8 bf16 elements) or a half-word (4 fp32 elements).
