@@ -219,6 +219,10 @@ __device__ __forceinline__ void stream_store16(uint16_t* p, uint32_t v)
 {
     asm volatile("global_store_short %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
+__device__ __forceinline__ void stream_store8(uint8_t* p, uint32_t v)  // low byte of v
+{
+    asm volatile("global_store_byte %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
 
 // The packed codes of one vector: a dword (8 bf16 elements) or a half-word (4 fp32 elements).
 template <bool BF16>
@@ -620,10 +624,10 @@ __global__ __launch_bounds__(kWave) void relu_fwd_kernel(const u32x4* x, u32x4* 
     }
     // every lane of the wave takes part in the shuffle
     if (BF16) {
-        if (i * EPV < n) mask[i] = (uint8_t)bits;
+        if (i * EPV < n) stream_store8(mask + i, bits);  // sc1 like the code stores: 1 % over a plain store
     } else {
         uint32_t other = (uint32_t)__shfl_xor((int)bits, 1, kWave);
-        if ((threadIdx.x & 1) == 0 && i * EPV < n) mask[i >> 1] = (uint8_t)(bits | (other << 4));
+        if ((threadIdx.x & 1) == 0 && i * EPV < n) stream_store8(mask + (i >> 1), bits | (other << 4));
     }
 }
 
