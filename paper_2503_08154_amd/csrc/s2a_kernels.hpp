@@ -196,7 +196,9 @@ __device__ __forceinline__ float gelu(float x) { return BF16 ? gelu_fast<ACT>(x)
 // stores of the packed codes (4 or 2 bytes per lane) carry "sc1" only: written
 // through at device scope but without the streaming hint.  With nt on them the
 // forward kernels ran 3-5 % slower (ViT-L bf16 80.3 -> 83.3 % of peak, ViT-G
-// fp32 83.3 -> 87.7 %); plain write-back stores come out between the two.  The
+// fp32 83.3 -> 87.7 %); plain write-back stores come out between the two, and
+// the same holds for the softmax codes although those leave as 16-byte vectors
+// (forward 2-4 % faster without nt on them).  The
 // compiler offers no source-level spelling for these combinations without also
 // serialising the stores, so the store instructions are written out.
 __device__ __forceinline__ u32x4 stream_load128(const u32x4* p) { return __builtin_nontemporal_load(p); }
@@ -210,6 +212,12 @@ __device__ __forceinline__ void stream_store128(u32x4* p, u32x4 v)
     // compiler inserts the wait for stores it emits itself, but it cannot see into this string
     // (seen as a few garbage elements per some launches of a loop that refills the registers).
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+}
+// 16 bytes of packed codes (the staged softmax writes its code bytes as whole vectors): the
+// codes' policy, with the same wait after a wide store.
+__device__ __forceinline__ void stream_store128_codes(u32x4* p, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void stream_store32(uint32_t* p, uint32_t v)
 {
@@ -870,7 +878,7 @@ __device__ __forceinline__ void stage_in(const void* src, unsigned char* lds, in
 // The reverse copy.  Vectors that lie wholly inside [a, b) are stored as such;
 // the ragged first and last vector belong partly to other blocks and are
 // written element by element, one element per lane.
-template <int UNIT, int BLOCK>
+template <int UNIT, int BLOCK, bool CODES = false>
 __device__ __forceinline__ void stage_out(void* dst, const unsigned char* lds, int64_t a, int64_t b)
 {
     const int64_t a_dn = a & ~(int64_t)15;
@@ -880,7 +888,10 @@ __device__ __forceinline__ void stage_out(void* dst, const unsigned char* lds, i
     const int tid = (int)threadIdx.x;
     const int i0 = (int)(((uintptr_t)g0 >> 4) & 15);  // 256-byte aligned windows, as in stage_in
     for (int i = tid - i0; i < last_full; i += BLOCK)
-        if (i >= first_full) stream_store128((u32x4*)(g0 + 16 * i), *(const u32x4*)(lds + 16 * i));
+        if (i >= first_full) {
+            const u32x4 v = *(const u32x4*)(lds + 16 * i);
+            if (CODES) stream_store128_codes((u32x4*)(g0 + 16 * i), v); else stream_store128((u32x4*)(g0 + 16 * i), v);
+        }
     constexpr int PER = 16 / UNIT;
     if (tid < 2 * PER) {
         const bool tail = tid >= PER;
@@ -1070,7 +1081,7 @@ __global__ __launch_bounds__(BLOCK) void softmax_fwd_staged(const void* x, void*
     }  // pass
     __syncthreads();
     stage_out<ES, BLOCK>(y, lds, xa, xb);
-    stage_out<1, BLOCK>(codes, lds + data_bytes, ca, cb);
+    stage_out<1, BLOCK, true>(codes, lds + data_bytes, ca, cb);
 }
 
 template <bool BF16, int G, int PASSES, int SLOTS, int BLOCK>
