@@ -122,9 +122,10 @@ int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int d
  *           inputs clip to -2 and take part in the minimum.  n == 0 leaves
  *           lo = scale = 0.
  *
- * Forward enqueues three kernels on `stream` (per-block min/max, the reduction
- * of those to the range and the levels, the forward kernel proper) and reads x
- * twice; no atomics are used, so the result does not depend on scheduling.
+ * Forward enqueues two kernels on `stream` (per-block min/max; the forward
+ * kernel proper, which reduces those to the range and leaves the levels in
+ * qstate) and reads x twice; both run for n == 0 as well.  No atomics are used,
+ * so the result does not depend on scheduling.
  * Everything else is as for
  * s2a_act_fwd / s2a_act_bwd.  When the tensor has elements beyond both clip
  * limits the results equal the fixed-range entry points'.

@@ -92,20 +92,28 @@ bool vector_grid(int64_t n, int64_t* nvec, unsigned* blocks)
     return true;
 }
 
+// DYN: the kernel's first wave also completes qstate, so at least one block runs even for n == 0.
 template <bool BF16, bool DYN, int ACT = s2a::kActGelu>
-int launch_fwd(const void* x, void* y, uint8_t* codes, const float* qs, int64_t n, hipStream_t st)
+int launch_fwd(const void* x, void* y, uint8_t* codes, float* qs, int64_t n, hipStream_t st)
 {
     if (aligned(x, 16) && aligned(y, 16) && aligned(codes, 4)) {
         int64_t nvec;
         unsigned blocks;
         if (!vector_grid<BF16>(n, &nvec, &blocks)) return S2A_ERR_SIZE;
+        if (DYN && blocks == 0) blocks = 1;
         return checked_launch([&] {
-            s2a::fwd_kernel<BF16, DYN, ACT><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
-                (const s2a::u32x4*)x, (s2a::u32x4*)y, codes, qs, n, nvec);
+            if constexpr (DYN)
+                s2a::fwd_dyn_kernel<BF16><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+                    (const s2a::u32x4*)x, (s2a::u32x4*)y, codes, qs, n, nvec);
+            else
+                s2a::fwd_kernel<BF16, ACT><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+                    (const s2a::u32x4*)x, (s2a::u32x4*)y, codes, n, nvec);
         });
     }
+    unsigned blocks = pair_grid(n);
+    if (DYN && blocks == 0) blocks = 1;
     return checked_launch([&] {
-        s2a::fwd_kernel_unaligned<BF16, DYN, ACT><<<dim3(pair_grid(n)), dim3(s2a::kBlock), 0, st>>>(x, y, codes, qs, n);
+        s2a::fwd_kernel_unaligned<BF16, DYN, ACT><<<dim3(blocks), dim3(s2a::kBlock), 0, st>>>(x, y, codes, qs, n);
     });
 }
 
@@ -128,7 +136,7 @@ int launch_bwd(const void* dy, const uint8_t* codes, void* dx, const float* qs, 
     });
 }
 
-// The two launches that measure the range of x and prepare qstate.
+// The launch that measures the range of x: per-block minima and maxima into qstate.
 template <bool BF16>
 int launch_range(const void* x, float* qs, int64_t n, hipStream_t st)
 {
@@ -138,15 +146,11 @@ int launch_range(const void* x, float* qs, int64_t n, hipStream_t st)
     int64_t blocks = (items + s2a::kRangeBlock - 1) / s2a::kRangeBlock;
     if (blocks > s2a::kRangeBlocks) blocks = s2a::kRangeBlocks;  // grid-stride beyond
     if (blocks < 1) blocks = 1;
-    int rc = checked_launch([&] {
+    return checked_launch([&] {
         if (al)
             s2a::range_minmax_kernel<BF16, true><<<dim3((unsigned)blocks), dim3(s2a::kRangeBlock), 0, st>>>(x, qs, n);
         else
             s2a::range_minmax_kernel<BF16, false><<<dim3((unsigned)blocks), dim3(s2a::kRangeBlock), 0, st>>>(x, qs, n);
-    });
-    if (rc != S2A_OK) return rc;
-    return checked_launch([&] {
-        s2a::range_finalize_kernel<<<dim3(1), dim3(s2a::kWave), 0, st>>>(qs, (int)blocks);
     });
 }
 
@@ -486,9 +490,9 @@ int s2a_act_fwd_dyn(const void* x, void* y, uint8_t* codes, float* qstate, int64
     if (!qstate) return S2A_ERR_NULL;
     if (((uintptr_t)qstate & 3u) != 0) return S2A_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    // n == 0 still leaves a defined state behind: min = max = 0, scale 0
+    // n == 0 still leaves a defined state behind (min = max = 0, scale 0): both launches run
     rc = dtype == S2A_BF16 ? launch_range<true>(x, qstate, n, st) : launch_range<false>(x, qstate, n, st);
-    if (rc != S2A_OK || n == 0) return rc;
+    if (rc != S2A_OK) return rc;
     return dtype == S2A_BF16 ? launch_fwd<true, true>(x, y, codes, qstate, n, st)
                              : launch_fwd<false, true>(x, y, codes, qstate, n, st);
 }

@@ -134,7 +134,7 @@ template <int ACT>
 struct BinFixed {
     __device__ __forceinline__ uint32_t operator()(float x) const { return bin_affine(x, Act<ACT>::bin_scale, 8.0f); }
 };
-// Measured range: scale and offset prepared by range_finalize_kernel.
+// Measured range: scale and offset from range_reduce.
 struct BinRange {
     float scale, offset;
     __device__ __forceinline__ uint32_t operator()(float x) const { return bin_affine(x, scale, offset); }
@@ -244,6 +244,84 @@ __device__ __forceinline__ void store_codes(uint8_t* codes, int64_t v, uint32_t 
     if (BF16) stream_store32((uint32_t*)codes + v, c); else stream_store16((uint16_t*)codes + v, c);
 }
 
+// ---------------------------------------------------------- cross-lane ----
+
+// Cross-lane moves inside a row of 16 lanes as DPP operand modifiers (no LDS
+// traffic, one VALU op each): swap with the neighbour (xor 1), with the other
+// pair of the quad (xor 2), mirror the 8 / the 16 lanes of a half row / row.
+// After the quads agree, the two mirrors pair every lane with one from the
+// other half, so for all-reduce purposes they act as xor 4 and xor 8.  Every
+// lane of the wave must be active.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, dpp_move<CTRL>(__builtin_bit_cast(int, v)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v)
+{
+    uint64_t u = __builtin_bit_cast(uint64_t, v);
+    uint32_t lo = (uint32_t)dpp_move<CTRL>((int)(uint32_t)u), hi = (uint32_t)dpp_move<CTRL>((int)(uint32_t)(u >> 32));
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+// v_max_f32 / v_min_f32 as single instructions.  (The portable fmaxf / fminf
+// first re-quiet every operand the compiler cannot prove canonical -- here all
+// of them, since they come from bit patterns -- which doubles the op count.)
+// NaN operands lose against numbers, as with fmaxf / fminf.
+__device__ __forceinline__ float vmax(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmin(float a, float b)
+{
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// All-reduce over the G lanes of a row group; F(a, b) is the (commutative) combiner.
+template <int G, typename T, typename F>
+__device__ __forceinline__ T group_reduce(T v, F f)
+{
+    v = f(v, dpp_move<kDppXor1>(v));
+    v = f(v, dpp_move<kDppXor2>(v));
+    if (G >= 8) v = f(v, dpp_move<kDppHalfMirror>(v));
+    if (G >= 16) v = f(v, dpp_move<kDppMirror>(v));
+    if (G >= 32) v = f(v, __shfl_xor(v, 16, kWave));
+    if (G >= 64) v = f(v, __shfl_xor(v, 32, kWave));
+    return v;
+}
+// A DPP operand must not be read within two wait states of the VALU write that produced it.
+// The compiler spaces the instructions it emits itself, but it does not look into asm strings,
+// so a value that comes out of vmax / vmin / vmax3 / vmin3 passes through this before a
+// cross-lane move reads it: the asm both waits and is the value's last definition.
+__device__ __forceinline__ float settled(float v)
+{
+    asm("s_nop 1" : "+v"(v));
+    return v;
+}
+template <int G>
+__device__ __forceinline__ float group_max(float v)
+{
+    return group_reduce<G>(settled(v), [](float a, float b) { return settled(vmax(a, b)); });
+}
+template <int G>
+__device__ __forceinline__ float group_min(float v)
+{
+    return group_reduce<G>(settled(v), [](float a, float b) { return settled(vmin(a, b)); });
+}
+template <int G, typename T>
+__device__ __forceinline__ T group_sum(T v) { return group_reduce<G>(v, [](T a, T b) { return a + b; }); }
+
 // ------------------------------------------------- element-wise pieces ----
 
 // Elements [first, n) with first even: one code byte per pair, pad nibble 0.
@@ -325,54 +403,6 @@ constexpr int kRangeBlocks = 256, kRangeBlock = 1024;
 constexpr int kQsMin = 2, kQsScale = 3, kQsInv = 4, kQsOff = 5, kQsTable = 16, kQsPartMin = 32,
               kQsPartMax = 32 + kRangeBlocks, kQsFloats = 32 + 2 * kRangeBlocks;
 
-// Vector kernel.  Requires x, y 16-byte aligned and codes 4-byte aligned.
-// x and y may be the same buffer (a lane loads its vector before it stores
-// it), so neither is declared restrict.
-//   DYN    false: fixed range [-2, 2]; true: range read from qs (see above)
-//   nvec   number of full vectors, n / EPV
-//   grid   ceil((nvec + (n % EPV != 0)) / kWave) blocks of kWave lanes
-template <bool BF16, bool DYN, int ACT>
-__global__ __launch_bounds__(kWave) void fwd_kernel(const u32x4* x, u32x4* y,
-                                                    uint8_t* __restrict__ codes,
-                                                    const float* __restrict__ qs, int64_t n,
-                                                    int64_t nvec)
-{
-    constexpr int EPV = BF16 ? 8 : 4;
-    typedef typename std::conditional<DYN, BinRange, BinFixed<ACT>>::type Bin;
-    Bin bin;
-    if constexpr (DYN) bin = BinRange{qs[kQsInv], qs[kQsOff]};
-    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
-    if (i < nvec) {
-        // A wave that is about to issue its load or its stores goes ahead of the waves that are
-        // in their arithmetic: the memory system is the bottleneck, so its requests should never
-        // wait for an issue slot.  Measured: fp32 forward 87.1 -> 85.5 us at the ViT-G shape
-        // (82.2 -> 83.7 % of peak); no change for bf16, whose arithmetic is lighter.
-        __builtin_amdgcn_s_setprio(3);
-        u32x4 v = stream_load128(x + i);
-        __builtin_amdgcn_s_setprio(0);
-        uint32_t c = fwd_vector<BF16, ACT>(v, bin);
-        __builtin_amdgcn_s_setprio(3);
-        stream_store128(y + i, v);
-        store_codes<BF16>(codes, i, c);
-    } else if (i == nvec) {  // one lane finishes the n % EPV leftover elements
-        fwd_pairs<BF16, ACT>(x, y, codes, bin, nvec * EPV, n, 0, 1);
-    }
-}
-
-// Any alignment: one lane per code byte, grid-stride.
-template <bool BF16, bool DYN, int ACT>
-__global__ __launch_bounds__(kBlock) void fwd_kernel_unaligned(const void* x, void* y,
-                                                               uint8_t* codes,
-                                                               const float* __restrict__ qs,
-                                                               int64_t n)
-{
-    typedef typename std::conditional<DYN, BinRange, BinFixed<ACT>>::type Bin;
-    Bin bin;
-    if constexpr (DYN) bin = BinRange{qs[kQsInv], qs[kQsOff]};
-    fwd_pairs<BF16, ACT>(x, y, codes, bin, 0, n, (int64_t)blockIdx.x * kBlock + threadIdx.x,
-                    (int64_t)gridDim.x * kBlock);
-}
-
 // --------------------------------------------- measured range (Eq. 8) -----
 
 // clip(x, -2, 2) with NaN -> -2 (a value below the range), as in the forward binning.
@@ -409,7 +439,7 @@ __device__ __forceinline__ void block_minmax(float& lo, float& hi)
 // walks its own contiguous share of the 16-byte vectors (of the elements when
 // ALIGNED is false) with two predicated loads in flight per lane, and leaves
 // its pair in qs[kQsPartMin + b] and qs[kQsPartMax + b] (+inf / -inf if it saw
-// no element).  The loads are ordinary cached loads on purpose: a tensor that
+// no element); all kRangeBlocks slots are written whatever the grid size.  The loads are ordinary cached loads on purpose: a tensor that
 // fits the 256 MB on-die cache is then still there when the forward kernel
 // reads it again (measured: the forward kernel takes 32.3 us instead of 36.1 us
 // at the ViT-L shape).
@@ -465,50 +495,165 @@ __global__ __launch_bounds__(kRangeBlock) void range_minmax_kernel(const void* x
         qs[kQsPartMin + blockIdx.x] = lo;
         qs[kQsPartMax + blockIdx.x] = hi;
     }
+    // a grid smaller than kRangeBlocks (small tensors): the remaining slots read as "no element"
+    for (int p = (int)(gridDim.x + blockIdx.x * kRangeBlock + threadIdx.x); p < kRangeBlocks;
+         p += (int)(gridDim.x * kRangeBlock)) {
+        qs[kQsPartMin + p] = __builtin_inff();
+        qs[kQsPartMax + p] = -__builtin_inff();
+    }
 }
 
-// Pass 2: one wave reduces the `nparts` pairs and turns (min, max) into the
-// scale, the binning constants and the 16 derivative levels
-// D[k] = sigma(1.702 xhat_k) + 0.22 sin(1.5 xhat_k), xhat_k = min + k * scale
-// (Eq. 9, Eq. 12), all in double, rounded once.  An empty tensor gives
-// min = max = 0.  A single wave: no LDS, no barrier.  The launch is all
-// latency (about 4.6 us, most of it the kernel boundary and the double
-// precision exp and sin; a 1024-lane block takes the same time).
-__global__ __launch_bounds__(kWave) void range_finalize_kernel(float* qs, int nparts)
+// Pass 2 has no launch of its own: every wave of the forward kernel reduces
+// the kRangeBlocks pairs itself (2 KiB that stay in the vector cache) and turns
+// (min, max) into the binning constants, all waves by the same instructions and
+// therefore to the same bits.  A launch in between costs 4.6 us at any size
+// (kernel boundary plus latency), 8 % of the whole pass at the ViT-L shape.
+// The first wave of the grid also leaves min, scale, the constants and the 16
+// derivative levels in qs for the backward pass (range_publish).
+struct RangeParts {
+    float lo[kRangeBlocks / kWave], hi[kRangeBlocks / kWave];
+};
+struct RangeBin {
+    BinRange bin;
+    double lo, width;  // min and max - min of the clipped tensor (0, 0 for an empty one)
+};
+// The loads alone, so that a kernel can put its own first load behind them and
+// reduce while that one is in flight (loads return in order).
+__device__ __forceinline__ RangeParts range_parts(const float* qs)
 {
-    float lo = __builtin_inff(), hi = -__builtin_inff();
-    constexpr int PER = kRangeBlocks / kWave;  // all loads of a lane in flight together
-    float plo[PER], phi[PER];
+    const int lane = (int)threadIdx.x & (kWave - 1);
+    RangeParts p;
 #pragma unroll
-    for (int q = 0; q < PER; ++q) {
-        const int p = q * kWave + (int)threadIdx.x;
-        plo[q] = p < nparts ? qs[kQsPartMin + p] : __builtin_inff();
-        phi[q] = p < nparts ? qs[kQsPartMax + p] : -__builtin_inff();
+    for (int q = 0; q < kRangeBlocks / kWave; ++q) {
+        p.lo[q] = qs[kQsPartMin + q * kWave + lane];
+        p.hi[q] = qs[kQsPartMax + q * kWave + lane];
     }
+    return p;
+}
+// Every lane of the wave must be active (cross-lane moves).
+__device__ __forceinline__ RangeBin range_reduce(const RangeParts& part)
+{
+    float lo = part.lo[0], hi = part.hi[0];
 #pragma unroll
-    for (int q = 0; q < PER; ++q) {
-        lo = fminf(lo, plo[q]);
-        hi = fmaxf(hi, phi[q]);
+    for (int q = 1; q < kRangeBlocks / kWave; ++q) {
+        lo = vmin(lo, part.lo[q]);
+        hi = vmax(hi, part.hi[q]);
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {  // butterfly: every lane ends with the result
-        lo = fminf(lo, __shfl_xor(lo, off, kWave));
-        hi = fmaxf(hi, __shfl_xor(hi, off, kWave));
-    }
+    lo = group_min<kWave>(lo);
+    hi = group_max<kWave>(hi);
     const bool empty = !(lo <= hi);
-    const double dlo = empty ? 0.0 : (double)lo, dhi = empty ? 0.0 : (double)hi;
-    const double scale = (dhi - dlo) / 15.0;
-    const int k = threadIdx.x;
-    if (k < 16) {
-        double xh = dlo + scale * (double)k;
-        qs[kQsTable + k] = (float)(1.0 / (1.0 + exp(-1.702 * xh)) + 0.22 * sin(1.5 * xh));
+    RangeBin r;
+    r.lo = empty ? 0.0 : (double)lo;
+    r.width = (empty ? 0.0 : (double)hi) - r.lo;
+    const double inv = r.width > 0.0 ? 15.0 / r.width : 0.0;
+    r.bin = BinRange{(float)inv, (float)(0.5 - r.lo * inv)};
+    return r;
+}
+// One wave: min, scale, the binning constants and the levels
+// D[k] = sigma(1.702 xhat_k) + 0.22 sin(1.5 xhat_k), xhat_k = min + k * scale
+// (Eq. 9, Eq. 12), in double, rounded once.
+__device__ __forceinline__ void range_publish(float* qs, const RangeBin& r)
+{
+    const int lane = (int)threadIdx.x & (kWave - 1);
+    const double scale = r.width / 15.0;
+    if (lane < 16) {
+        const double xh = r.lo + scale * (double)lane;
+        qs[kQsTable + lane] = (float)(1.0 / (1.0 + exp(-1.702 * xh)) + 0.22 * sin(1.5 * xh));
     }
-    if (k == 0) {
-        double inv = scale > 0.0 ? 1.0 / scale : 0.0;
-        qs[kQsMin] = (float)dlo;
+    if (lane == 0) {
+        qs[kQsMin] = (float)r.lo;
         qs[kQsScale] = (float)scale;
-        qs[kQsInv] = (float)inv;
-        qs[kQsOff] = (float)(0.5 - dlo * inv);
+        qs[kQsInv] = r.bin.scale;
+        qs[kQsOff] = r.bin.offset;
+    }
+}
+
+// ------------------------------------------------------ forward kernels ----
+
+// Vector kernel.  Requires x, y 16-byte aligned and codes 4-byte aligned.
+// x and y may be the same buffer (a lane loads its vector before it stores
+// it), so neither is declared restrict.
+//   nvec   number of full vectors, n / EPV
+//   grid   ceil((nvec + (n % EPV != 0)) / kWave) blocks of kWave lanes
+template <bool BF16, int ACT>
+__global__ __launch_bounds__(kWave) void fwd_kernel(const u32x4* x, u32x4* y,
+                                                    uint8_t* __restrict__ codes, int64_t n,
+                                                    int64_t nvec)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    const BinFixed<ACT> bin;
+    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    if (i < nvec) {
+        // A wave that is about to issue its load or its stores goes ahead of the waves that are
+        // in their arithmetic: the memory system is the bottleneck, so its requests should never
+        // wait for an issue slot.  Measured: fp32 forward 87.1 -> 85.5 us at the ViT-G shape
+        // (82.2 -> 83.7 % of peak); no change for bf16, whose arithmetic is lighter.
+        __builtin_amdgcn_s_setprio(3);
+        u32x4 v = stream_load128(x + i);
+        __builtin_amdgcn_s_setprio(0);
+        uint32_t c = fwd_vector<BF16, ACT>(v, bin);
+        __builtin_amdgcn_s_setprio(3);
+        stream_store128(y + i, v);
+        store_codes<BF16>(codes, i, c);
+    } else if (i == nvec) {  // one lane finishes the n % EPV leftover elements
+        fwd_pairs<BF16, ACT>(x, y, codes, bin, nvec * EPV, n, 0, 1);
+    }
+}
+
+// The same with the measured range (GELU only): qs holds the partial minima
+// and maxima of the range pass.  A wave that lies wholly inside the tensor (a
+// scalar branch) requests the partials, then its vector of x, and reduces the
+// partials while x is on its way.  The grid has at least one block, also for
+// n = 0, so that qs is always completed.
+template <bool BF16>
+__global__ __launch_bounds__(kWave) void fwd_dyn_kernel(const u32x4* x, u32x4* y,
+                                                        uint8_t* __restrict__ codes,
+                                                        float* __restrict__ qs, int64_t n,
+                                                        int64_t nvec)
+{
+    constexpr int EPV = BF16 ? 8 : 4;
+    const int64_t wave0 = (int64_t)blockIdx.x * kWave;
+    const int64_t i = wave0 + threadIdx.x;
+    const RangeParts part = range_parts(qs);
+    RangeBin r;
+    if (wave0 + kWave <= nvec) {
+        __builtin_amdgcn_s_setprio(3);
+        u32x4 v = stream_load128(x + i);
+        __builtin_amdgcn_s_setprio(0);
+        r = range_reduce(part);
+        uint32_t c = fwd_vector<BF16, kActGelu>(v, r.bin);
+        __builtin_amdgcn_s_setprio(3);
+        stream_store128(y + i, v);
+        store_codes<BF16>(codes, i, c);
+        __builtin_amdgcn_s_setprio(0);
+    } else {
+        r = range_reduce(part);
+        if (i < nvec) {
+            u32x4 v = stream_load128(x + i);
+            uint32_t c = fwd_vector<BF16, kActGelu>(v, r.bin);
+            stream_store128(y + i, v);
+            store_codes<BF16>(codes, i, c);
+        } else if (i == nvec) {
+            fwd_pairs<BF16, kActGelu>(x, y, codes, r.bin, nvec * EPV, n, 0, 1);
+        }
+    }
+    if (blockIdx.x == 0) range_publish(qs, r);
+}
+
+// Any alignment: one lane per code byte, grid-stride.  DYN: measured range as above.
+template <bool BF16, bool DYN, int ACT>
+__global__ __launch_bounds__(kBlock) void fwd_kernel_unaligned(const void* x, void* y,
+                                                               uint8_t* codes,
+                                                               float* __restrict__ qs,
+                                                               int64_t n)
+{
+    const int64_t pair0 = (int64_t)blockIdx.x * kBlock + threadIdx.x, stride = (int64_t)gridDim.x * kBlock;
+    if constexpr (DYN) {
+        const RangeBin r = range_reduce(range_parts(qs));
+        fwd_pairs<BF16, ACT>(x, y, codes, r.bin, 0, n, pair0, stride);
+        if (blockIdx.x == 0 && threadIdx.x < kWave) range_publish(qs, r);
+    } else {
+        fwd_pairs<BF16, ACT>(x, y, codes, BinFixed<ACT>(), 0, n, pair0, stride);
     }
 }
 
@@ -717,82 +862,6 @@ __global__ __launch_bounds__(kBlock) void relu_bwd_kernel_unaligned(const void* 
 // both codes into the byte it stores.
 constexpr int kSoftmaxSlots = 16;    // elements (fallback kernels) or element pairs (staged kernels) per lane at most
 constexpr int kSoftmaxMaxL = 64 * kSoftmaxSlots;
-
-// Cross-lane moves inside a row of 16 lanes as DPP operand modifiers (no LDS
-// traffic, one VALU op each): swap with the neighbour (xor 1), with the other
-// pair of the quad (xor 2), mirror the 8 / the 16 lanes of a half row / row.
-// After the quads agree, the two mirrors pair every lane with one from the
-// other half, so for all-reduce purposes they act as xor 4 and xor 8.  Every
-// lane of the wave must be active.
-template <int CTRL>
-__device__ __forceinline__ int dpp_move(int v)
-{
-    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v)
-{
-    return __builtin_bit_cast(float, dpp_move<CTRL>(__builtin_bit_cast(int, v)));
-}
-template <int CTRL>
-__device__ __forceinline__ double dpp_move(double v)
-{
-    uint64_t u = __builtin_bit_cast(uint64_t, v);
-    uint32_t lo = (uint32_t)dpp_move<CTRL>((int)(uint32_t)u), hi = (uint32_t)dpp_move<CTRL>((int)(uint32_t)(u >> 32));
-    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
-}
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
-
-// v_max_f32 / v_min_f32 as single instructions.  (The portable fmaxf / fminf
-// first re-quiet every operand the compiler cannot prove canonical -- here all
-// of them, since they come from bit patterns -- which doubles the op count.)
-// NaN operands lose against numbers, as with fmaxf / fminf.
-__device__ __forceinline__ float vmax(float a, float b)
-{
-    float r;
-    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-__device__ __forceinline__ float vmin(float a, float b)
-{
-    float r;
-    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-
-// All-reduce over the G lanes of a row group; F(a, b) is the (commutative) combiner.
-template <int G, typename T, typename F>
-__device__ __forceinline__ T group_reduce(T v, F f)
-{
-    v = f(v, dpp_move<kDppXor1>(v));
-    v = f(v, dpp_move<kDppXor2>(v));
-    if (G >= 8) v = f(v, dpp_move<kDppHalfMirror>(v));
-    if (G >= 16) v = f(v, dpp_move<kDppMirror>(v));
-    if (G >= 32) v = f(v, __shfl_xor(v, 16, kWave));
-    if (G >= 64) v = f(v, __shfl_xor(v, 32, kWave));
-    return v;
-}
-// A DPP operand must not be read within two wait states of the VALU write that produced it.
-// The compiler spaces the instructions it emits itself, but it does not look into asm strings,
-// so a value that comes out of vmax / vmin / vmax3 / vmin3 passes through this before a
-// cross-lane move reads it: the asm both waits and is the value's last definition.
-__device__ __forceinline__ float settled(float v)
-{
-    asm("s_nop 1" : "+v"(v));
-    return v;
-}
-template <int G>
-__device__ __forceinline__ float group_max(float v)
-{
-    return group_reduce<G>(settled(v), [](float a, float b) { return settled(vmax(a, b)); });
-}
-template <int G>
-__device__ __forceinline__ float group_min(float v)
-{
-    return group_reduce<G>(settled(v), [](float a, float b) { return settled(vmin(a, b)); });
-}
-template <int G, typename T>
-__device__ __forceinline__ T group_sum(T v) { return group_reduce<G>(v, [](T a, T b) { return a + b; }); }
 
 // exp(x - m) for x <= m.  The bf16 storage path takes the plain route.  The
 // fp32 storage path keeps 1e-6 relative accuracy down to the smallest results:
