@@ -144,6 +144,28 @@ def test_degenerate_tensors(dtype):
     assert qs[2] == 0.0 and qs[3] == 0.0 and bq.canaries_intact()
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_qstate_reused_by_a_smaller_tensor(dtype):
+    """The same qstate serves a large tensor (every per-block slot written) and then small ones whose
+    range pass runs fewer blocks: nothing of the first call may leak into the later ranges.  Also
+    with the slots pre-filled by extreme finite values."""
+    st = torch.cuda.current_stream().cuda_stream
+    es = gu.esize(dtype)
+    bq = gu.Buf(4 * s2a.QSTATE_FLOATS)
+    bq.upload(np.tile(np.array([-1e30, 1e30], np.float32), s2a.QSTATE_FLOATS // 2))
+    big = _draw(600_000, "wide", dtype, seed=41)
+    for n, x in [(600_000, big), (5000, _draw(5000, "one_sided", dtype, seed=42)), (3, wl.to_storage(np.array([0.5, 0.25, 0.75]), dtype)),
+                 (70_000, _draw(70_000, "narrow", dtype, seed=43))]:
+        bx, by, bc = gu.Buf(n * es).upload(x), gu.Buf(n * es), gu.Buf((n + 1) // 2)
+        s2a.act_fwd_dyn(bx.ptr, by.ptr, bc.ptr, bq.ptr, n, dtype, st)
+        torch.cuda.synchronize()
+        _, code_ref, _, near, qmin, qscale = oracle.fwd_dyn(x, dtype, band=parity.BAND)
+        qs = bq.download(np.float32)
+        assert qs[2] == np.float32(qmin) and qs[3] == np.float32(qscale), n
+        parity.check_codes(bc.download(np.uint8), code_ref, near, n)
+        assert bq.canaries_intact()
+
+
 @pytest.mark.parametrize("name", ["vit_b16", "vit_g14_f32"])
 def test_workload_full_size(name):
     """Full-size launch; the activations are scaled down so that no element reaches a
