@@ -11,7 +11,6 @@
 
 namespace {
 
-
 struct TableState {
     bool ready = false;
     s2a::QTable dev;   // fp32 derivative levels handed to kernels by value
@@ -52,10 +51,7 @@ int check_args(const void* a, const void* b, const void* c, int64_t n, int dtype
 int check_common(const void* a, const void* b, const void* c, int64_t n, int dtype)
 {
     if (!g_table.ready) return S2A_ERR_NOT_INIT;
-    if (dtype != S2A_F32 && dtype != S2A_BF16) return S2A_ERR_DTYPE;
-    if (n < 0) return S2A_ERR_SIZE;
-    if (n > 0 && (!a || !b || !c)) return S2A_ERR_NULL;
-    return S2A_OK;
+    return check_args(a, b, c, n, dtype);
 }
 
 bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
@@ -235,21 +231,14 @@ int softmax_pair_group(int64_t L)
     return g;
 }
 
-// Row groups per block of the staged kernels, by measurement at the ViT-B/16
-// attention shape.
-template <bool BF16>
-constexpr int fwd_passes() { return 1; }
-template <bool BF16>
-constexpr int bwd_passes() { return 1; }
-
 // LDS bytes of one staged softmax block: the data span (+ up to 15 bytes of
 // lead-in and padding to a vector), then the codes span.
 // Lanes per block of the staged kernels: 256 measured fastest of 64 .. 1024.
 constexpr int kStagedBlock = 256;
 template <bool BF16, int G>
-void softmax_lds(int L, int passes, int* data_bytes, int* total_bytes)
+void softmax_lds(int L, int* data_bytes, int* total_bytes)
 {
-    const int rpb = passes * kStagedBlock / G, es = BF16 ? 2 : 4;
+    const int rpb = kStagedBlock / G, es = BF16 ? 2 : 4;
     *data_bytes = ((rpb * L * es + 15 + 15) / 16) * 16;
     *total_bytes = *data_bytes + ((rpb * ((L + 1) / 2) + 15 + 15) / 16) * 16;
 }
@@ -266,15 +255,14 @@ template <bool BF16, int G>
 int launch_softmax_fwd_staged(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
                               hipStream_t st)
 {
-    constexpr int P = fwd_passes<BF16>();
-    const int rpb = P * kStagedBlock / G;
+    const int rpb = kStagedBlock / G;
     const int64_t blocks = (rows + rpb - 1) / rpb;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     int data_bytes, total;
-    softmax_lds<BF16, G>(L, P, &data_bytes, &total);
+    softmax_lds<BF16, G>(L, &data_bytes, &total);
     return checked_launch([&] {
         with_slots<G, pair_slots<BF16>()>(((L + 1) / 2 + G - 1) / G, [&](auto sc) {
-            s2a::softmax_fwd_staged<BF16, G, P, decltype(sc)::value, kStagedBlock>
+            s2a::softmax_fwd_staged<BF16, G, decltype(sc)::value, kStagedBlock>
                 <<<dim3((unsigned)blocks), dim3(kStagedBlock), total, st>>>(x, y, codes, qp, rows, L, data_bytes);
         });
     });
@@ -283,15 +271,14 @@ template <bool BF16, int G>
 int launch_softmax_bwd_staged(const void* dy, const uint8_t* codes, const float* qp, void* dx,
                               int64_t rows, int L, hipStream_t st)
 {
-    constexpr int P = bwd_passes<BF16>();
-    const int rpb = P * kStagedBlock / G;
+    const int rpb = kStagedBlock / G;
     const int64_t blocks = (rows + rpb - 1) / rpb;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     int data_bytes, total;
-    softmax_lds<BF16, G>(L, P, &data_bytes, &total);
+    softmax_lds<BF16, G>(L, &data_bytes, &total);
     return checked_launch([&] {
         with_slots<G, pair_slots<BF16>()>(((L + 1) / 2 + G - 1) / G, [&](auto sc) {
-            s2a::softmax_bwd_staged<BF16, G, P, decltype(sc)::value, kStagedBlock>
+            s2a::softmax_bwd_staged<BF16, G, decltype(sc)::value, kStagedBlock>
                 <<<dim3((unsigned)blocks), dim3(kStagedBlock), total, st>>>(dy, codes, qp, dx, rows, L, data_bytes);
         });
     });

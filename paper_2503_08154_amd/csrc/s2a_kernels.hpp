@@ -1040,8 +1040,7 @@ struct RowExp {
     }
 };
 
-// PASSES = row groups per block: more bytes in flight per block, fewer blocks.
-template <bool BF16, int G, int PASSES, int SLOTS, int BLOCK>
+template <bool BF16, int G, int SLOTS, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void softmax_fwd_staged(const void* x, void* y,
                                                                     uint8_t* codes,
                                                                     float* __restrict__ qparams,
@@ -1049,8 +1048,7 @@ __global__ __launch_bounds__(BLOCK) void softmax_fwd_staged(const void* x, void*
                                                                     int data_bytes)
 {
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr int RPP = BLOCK / G;   // rows per pass
-    constexpr int RPB = RPP * PASSES;        // rows per block
+    constexpr int RPB = BLOCK / G;           // rows per block
     constexpr int KL = SLOTS - 1;            // the only slot that can be partly empty
     constexpr int PS = 2 * G * ES;           // bytes between a lane's consecutive pairs
     extern __shared__ __align__(16) unsigned char lds[];
@@ -1068,92 +1066,89 @@ __global__ __launch_bounds__(BLOCK) void softmax_fwd_staged(const void* x, void*
     stage_in<ES, BLOCK>(x, lds, xa, xb, rows * L * ES);
     __syncthreads();
 
-#pragma unroll 1
-    for (int pass = 0; pass < PASSES; ++pass) {
-        const int lrow = pass * RPP + (int)threadIdx.x / G;
-        const bool live = lrow < nrows;
-        const int srow = live ? lrow : nrows - 1;
-        unsigned char* lx = lds + (int)(xa & 15) + (srow * L + 2 * l) * ES;  // this lane's first pair
-        unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + l;  // and its code byte
+    const int lrow = (int)threadIdx.x / G;
+    const bool live = lrow < nrows;
+    const int srow = live ? lrow : nrows - 1;
+    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + 2 * l) * ES;  // this lane's first pair
+    unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + l;  // and its code byte
 
-        // pass 1: load, row maximum and minimum
-        float a[SLOTS], b[SLOTS];
-        float m = -__builtin_inff(), xmin = __builtin_inff();
+    // pass 1: load, row maximum and minimum
+    float a[SLOTS], b[SLOTS];
+    float m = -__builtin_inff(), xmin = __builtin_inff();
+#pragma unroll
+    for (int k = 0; k < KL; ++k) {
+        a[k] = lds_in<BF16>(lx + k * PS);
+        b[k] = lds_in<BF16>(lx + k * PS + ES);
+    }
+    a[KL] = lds_in<BF16>(lx + o0);
+    b[KL] = lds_in<BF16>(lx + o1);
+#pragma unroll
+    for (int k = 0; k < SLOTS; ++k) {
+        m = vmax3(m, a[k], b[k]);
+        xmin = vmin3(xmin, a[k], b[k]);
+    }
+    m = group_max<G>(m);
+    xmin = group_min<G>(xmin);
+
+    // pass 2: exponentials and their sum
+    const RowExp<BF16> ex(m);
+    typedef typename std::conditional<BF16, float, double>::type acc_t;
+    acc_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < KL; ++k) {
+        a[k] = ex(a[k]);
+        b[k] = ex(b[k]);
+        sum += (acc_t)a[k];
+        sum += (acc_t)b[k];
+    }
+    a[KL] = has0 ? ex(a[KL]) : 0.0f;
+    b[KL] = has1 ? ex(b[KL]) : 0.0f;
+    sum += (acc_t)a[KL];
+    sum += (acc_t)b[KL];
+    sum = group_sum<G>(sum);
+    // reciprocals by v_rcp_f32 (1 ulp): a full division sequence costs a dozen instructions per lane
+    const float inv = BF16 ? __builtin_amdgcn_rcpf((float)sum) : (float)((acc_t)1 / sum);
+    // y is monotone in x, so its extremes are the images of the row's extremes
+    const float hi = ex(m) * inv;
+    const float lo = ex(xmin) * inv;
+    const float scale = (hi - lo) * (1.0f / 15.0f);
+    const float inv_scale = hi > lo ? 15.0f * __builtin_amdgcn_rcpf(hi - lo) : 0.0f;
+    if (live && l == 0) {
+        qparams[2 * (row0 + lrow)] = lo;
+        qparams[2 * (row0 + lrow) + 1] = scale;
+    }
+
+    // pass 3: y and the codes into LDS.  lo <= y <= hi and inv_scale is
+    // 15/(hi - lo) to 1 ulp, so (y - lo)*inv_scale + 0.5 stays below 15.5*(1 + 2^-22):
+    // the saturating conversion (floor; NaN and negatives -> 0) never exceeds 15.
+    auto quantize = [&](float yk) -> uint32_t {
+        float t = __builtin_fmaf(yk - lo, inv_scale, 0.5f);
+        uint32_t c;
+        asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));
+        return c;
+    };
+    if (live) {
 #pragma unroll
         for (int k = 0; k < KL; ++k) {
-            a[k] = lds_in<BF16>(lx + k * PS);
-            b[k] = lds_in<BF16>(lx + k * PS + ES);
+            const float ya = a[k] * inv, yb = b[k] * inv;
+            lds_out2<BF16>(lx + k * PS, ya, yb);
+            lc[k * G] = (uint8_t)(quantize(ya) | (quantize(yb) << 4));
         }
-        a[KL] = lds_in<BF16>(lx + o0);
-        b[KL] = lds_in<BF16>(lx + o1);
-#pragma unroll
-        for (int k = 0; k < SLOTS; ++k) {
-            m = vmax3(m, a[k], b[k]);
-            xmin = vmin3(xmin, a[k], b[k]);
+        const float ya = a[KL] * inv, yb = b[KL] * inv;
+        if (has1) {
+            lds_out2<BF16>(lx + KL * PS, ya, yb);
+            lc[KL * G] = (uint8_t)(quantize(ya) | (quantize(yb) << 4));
+        } else if (has0) {  // the row's last, unpaired element: the pad nibble is 0
+            lds_out<BF16>(lx + KL * PS, ya);
+            lc[KL * G] = (uint8_t)quantize(ya);
         }
-        m = group_max<G>(m);
-        xmin = group_min<G>(xmin);
-
-        // pass 2: exponentials and their sum
-        const RowExp<BF16> ex(m);
-        typedef typename std::conditional<BF16, float, double>::type acc_t;
-        acc_t sum = 0;
-#pragma unroll
-        for (int k = 0; k < KL; ++k) {
-            a[k] = ex(a[k]);
-            b[k] = ex(b[k]);
-            sum += (acc_t)a[k];
-            sum += (acc_t)b[k];
-        }
-        a[KL] = has0 ? ex(a[KL]) : 0.0f;
-        b[KL] = has1 ? ex(b[KL]) : 0.0f;
-        sum += (acc_t)a[KL];
-        sum += (acc_t)b[KL];
-        sum = group_sum<G>(sum);
-        // reciprocals by v_rcp_f32 (1 ulp): a full division sequence costs a dozen instructions per lane
-        const float inv = BF16 ? __builtin_amdgcn_rcpf((float)sum) : (float)((acc_t)1 / sum);
-        // y is monotone in x, so its extremes are the images of the row's extremes
-        const float hi = ex(m) * inv;
-        const float lo = ex(xmin) * inv;
-        const float scale = (hi - lo) * (1.0f / 15.0f);
-        const float inv_scale = hi > lo ? 15.0f * __builtin_amdgcn_rcpf(hi - lo) : 0.0f;
-        if (live && l == 0) {
-            qparams[2 * (row0 + lrow)] = lo;
-            qparams[2 * (row0 + lrow) + 1] = scale;
-        }
-
-        // pass 3: y and the codes into LDS.  lo <= y <= hi and inv_scale is
-        // 15/(hi - lo) to 1 ulp, so (y - lo)*inv_scale + 0.5 stays below 15.5*(1 + 2^-22):
-        // the saturating conversion (floor; NaN and negatives -> 0) never exceeds 15.
-        auto quantize = [&](float yk) -> uint32_t {
-            float t = __builtin_fmaf(yk - lo, inv_scale, 0.5f);
-            uint32_t c;
-            asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));
-            return c;
-        };
-        if (live) {
-#pragma unroll
-            for (int k = 0; k < KL; ++k) {
-                const float ya = a[k] * inv, yb = b[k] * inv;
-                lds_out2<BF16>(lx + k * PS, ya, yb);
-                lc[k * G] = (uint8_t)(quantize(ya) | (quantize(yb) << 4));
-            }
-            const float ya = a[KL] * inv, yb = b[KL] * inv;
-            if (has1) {
-                lds_out2<BF16>(lx + KL * PS, ya, yb);
-                lc[KL * G] = (uint8_t)(quantize(ya) | (quantize(yb) << 4));
-            } else if (has0) {  // the row's last, unpaired element: the pad nibble is 0
-                lds_out<BF16>(lx + KL * PS, ya);
-                lc[KL * G] = (uint8_t)quantize(ya);
-            }
-        }
-    }  // pass
+    }
     __syncthreads();
     stage_out<ES, BLOCK>(y, lds, xa, xb);
     stage_out<1, BLOCK, true>(codes, lds + data_bytes, ca, cb);
 }
 
-template <bool BF16, int G, int PASSES, int SLOTS, int BLOCK>
+template <bool BF16, int G, int SLOTS, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void softmax_bwd_staged(const void* dy,
                                                                     const uint8_t* codes,
                                                                     const float* __restrict__ qparams,
@@ -1161,8 +1156,7 @@ __global__ __launch_bounds__(BLOCK) void softmax_bwd_staged(const void* dy,
                                                                     int data_bytes)
 {
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr int RPP = BLOCK / G;
-    constexpr int RPB = RPP * PASSES;
+    constexpr int RPB = BLOCK / G;
     constexpr int KL = SLOTS - 1;
     constexpr int PS = 2 * G * ES;
     extern __shared__ __align__(16) unsigned char lds[];
@@ -1182,45 +1176,42 @@ __global__ __launch_bounds__(BLOCK) void softmax_bwd_staged(const void* dy,
     stage_in<1, BLOCK>(codes, lds + data_bytes, ca, cb, rows * rb);
     __syncthreads();
 
-#pragma unroll 1
-    for (int pass = 0; pass < PASSES; ++pass) {
-        const int lrow = pass * RPP + (int)threadIdx.x / G;
-        const bool live = lrow < nrows;
-        const int srow = live ? lrow : nrows - 1;
-        unsigned char* lx = lds + (int)(xa & 15) + (srow * L + 2 * l) * ES;
-        const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + l;
-        const float lo = qparams[2 * (row0 + srow)];
-        const float scale = qparams[2 * (row0 + srow) + 1];
+    const int lrow = (int)threadIdx.x / G;
+    const bool live = lrow < nrows;
+    const int srow = live ? lrow : nrows - 1;
+    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + 2 * l) * ES;
+    const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + l;
+    const float lo = qparams[2 * (row0 + srow)];
+    const float scale = qparams[2 * (row0 + srow) + 1];
 
-        float ya[SLOTS], yb[SLOTS], ga[SLOTS], gb[SLOTS];
+    float ya[SLOTS], yb[SLOTS], ga[SLOTS], gb[SLOTS];
 #pragma unroll
-        for (int k = 0; k < SLOTS; ++k) {
-            const uint32_t byte = lc[k < KL ? k * G : oc];
-            ya[k] = __builtin_fmaf((float)(byte & 15u), scale, lo);
-            yb[k] = __builtin_fmaf((float)(byte >> 4), scale, lo);
-            ga[k] = lds_in<BF16>(lx + (k < KL ? k * PS : o0));
-            gb[k] = lds_in<BF16>(lx + (k < KL ? k * PS + ES : o1));
-        }
-        float dot = 0.0f;
+    for (int k = 0; k < SLOTS; ++k) {
+        const uint32_t byte = lc[k < KL ? k * G : oc];
+        ya[k] = __builtin_fmaf((float)(byte & 15u), scale, lo);
+        yb[k] = __builtin_fmaf((float)(byte >> 4), scale, lo);
+        ga[k] = lds_in<BF16>(lx + (k < KL ? k * PS : o0));
+        gb[k] = lds_in<BF16>(lx + (k < KL ? k * PS + ES : o1));
+    }
+    float dot = 0.0f;
 #pragma unroll
-        for (int k = 0; k < KL; ++k) {
-            dot = __builtin_fmaf(ya[k], ga[k], dot);
-            dot = __builtin_fmaf(yb[k], gb[k], dot);
-        }
-        dot = has0 ? __builtin_fmaf(ya[KL], ga[KL], dot) : dot;
-        dot = has1 ? __builtin_fmaf(yb[KL], gb[KL], dot) : dot;
-        dot = group_sum<G>(dot);
+    for (int k = 0; k < KL; ++k) {
+        dot = __builtin_fmaf(ya[k], ga[k], dot);
+        dot = __builtin_fmaf(yb[k], gb[k], dot);
+    }
+    dot = has0 ? __builtin_fmaf(ya[KL], ga[KL], dot) : dot;
+    dot = has1 ? __builtin_fmaf(yb[KL], gb[KL], dot) : dot;
+    dot = group_sum<G>(dot);
 
-        if (live) {
+    if (live) {
 #pragma unroll
-            for (int k = 0; k < KL; ++k)
-                lds_out2<BF16>(lx + k * PS, ya[k] * (ga[k] - dot), yb[k] * (gb[k] - dot));
-            if (has1)
-                lds_out2<BF16>(lx + KL * PS, ya[KL] * (ga[KL] - dot), yb[KL] * (gb[KL] - dot));
-            else if (has0)
-                lds_out<BF16>(lx + KL * PS, ya[KL] * (ga[KL] - dot));
-        }
-    }  // pass
+        for (int k = 0; k < KL; ++k)
+            lds_out2<BF16>(lx + k * PS, ya[k] * (ga[k] - dot), yb[k] * (gb[k] - dot));
+        if (has1)
+            lds_out2<BF16>(lx + KL * PS, ya[KL] * (ga[KL] - dot), yb[KL] * (gb[KL] - dot));
+        else if (has0)
+            lds_out<BF16>(lx + KL * PS, ya[KL] * (ga[KL] - dot));
+    }
     __syncthreads();
     stage_out<ES, BLOCK>(dx, lds, xa, xb);
 }
