@@ -434,6 +434,16 @@ def main():
                 "buffer_sets": tw.layers, "slower": rf["kernel"],
             }
         out["target_shapes"] = targets
+        # the smallest configuration (2.6 MB per launch, 0.3 us at the roofline): a launch takes what a launch
+        # takes; reported, not a roofline figure
+        tw = wl.WORKLOADS["tiny"]
+        tw = wl.Workload(tw.name, tw.index, tw.dtype, tw.shapes, 64, tw.dist, tw.scale, tw.dy_scale)
+        r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False)
+        out["tiny_config"] = {
+            "workload": "tiny: f32 2x197x768", "buffer_sets": tw.layers, "bytes_per_launch": int(r["bytes_per_launch"]),
+            "fwd_us": round(r["fwd_us_per_launch"], 2), "bwd_us": round(r["bwd_us_per_launch"], 2),
+            "bound": "launch",
+        }
         # next row: the measured-range quantizer (Eq. 8 read literally).  Its forward reads x twice
         # (range pass, then the forward kernel), so its algorithmic bytes are 3e + 0.5 per element.
         tw = wl.WORKLOADS["vit_l16"]
