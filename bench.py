@@ -156,6 +156,47 @@ def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds
     return res
 
 
+def time_tiny(torch, steps: int, warmup: int):
+    """The smallest configuration over 64 buffer sets: the interval between launches enqueued one by
+    one, and the same 128 launches captured once in a HIP graph and replayed (the launch-bound case
+    that graphs are for; the entry points enqueue kernels only, so they can be captured)."""
+    tw = wl.WORKLOADS["tiny"]
+    tw = wl.Workload(tw.name, tw.index, tw.dtype, tw.shapes, 64, tw.dist, tw.scale, tw.dy_scale)
+    layers = build_layers(torch, tw, False)
+    launches = 2 * len(layers)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for _ in range(warmup):
+            run_step(layers, side.cuda_stream)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_step(layers, torch.cuda.current_stream().cuda_stream)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def wall(step):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    eager = wall(lambda: run_step(layers, stream))
+    replay = wall(graph.replay)
+    res = {
+        "workload": "tiny: f32 2x197x768, fwd then bwd over 64 buffer sets", "bound": "launch",
+        "bytes_per_launch": int(bytes_per_direction(layers[0].n, layers[0].dtype)),
+        "us_per_launch": round(eager * 1e6 / launches, 2),
+        "us_per_launch_graph_replay": round(replay * 1e6 / launches, 2),
+    }
+    del graph, layers
+    torch.cuda.empty_cache()
+    return res
+
+
 def time_copy_ceiling(torch, nbytes_total: float, sets: int, steps: int, warmup: int):
     """A plain streaming copy with the kernels' launch shape and memory instructions
     (s2a_stream_copy) moving the same bytes per launch as an activation kernel: half in, half out."""
@@ -434,16 +475,8 @@ def main():
                 "buffer_sets": tw.layers, "slower": rf["kernel"],
             }
         out["target_shapes"] = targets
-        # the smallest configuration (2.6 MB per launch, 0.3 us at the roofline): a launch takes what a launch
-        # takes; reported, not a roofline figure
-        tw = wl.WORKLOADS["tiny"]
-        tw = wl.Workload(tw.name, tw.index, tw.dtype, tw.shapes, 64, tw.dist, tw.scale, tw.dy_scale)
-        r = time_workload(torch, tw, max(5, args.steps // 2), max(5, args.warmup), distinct_seeds=False)
-        out["tiny_config"] = {
-            "workload": "tiny: f32 2x197x768", "buffer_sets": tw.layers, "bytes_per_launch": int(r["bytes_per_launch"]),
-            "fwd_us": round(r["fwd_us_per_launch"], 2), "bwd_us": round(r["bwd_us_per_launch"], 2),
-            "bound": "launch",
-        }
+        # the smallest configuration (2.6 MB per launch, 0.3 us at the roofline): reported, not a roofline figure
+        out["tiny_config"] = time_tiny(torch, max(5, args.steps // 2), max(5, args.warmup))
         # next row: the measured-range quantizer (Eq. 8 read literally).  Its forward reads x twice
         # (range pass, then the forward kernel), so its algorithmic bytes are 3e + 0.5 per element.
         tw = wl.WORKLOADS["vit_l16"]
