@@ -148,6 +148,48 @@ def test_side_stream():
     _fwd_bwd_check(x, dy, wl.BF16, stream=s)
 
 
+def test_two_streams_in_flight_together():
+    """Launches of every kind interleaved on two streams with no synchronisation in between (the
+    library keeps no per-call device state, the measured-range variant only its caller's qstate):
+    each stream's results match the oracle."""
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    jobs = []
+    for k, (dtype, n) in enumerate([(wl.BF16, 3_000_003), (wl.F32, 2_500_001)]):
+        es = gu.esize(dtype)
+        x = wl.draw_x(n, "normal", 1.2, dtype, seed=900 + k)
+        dy = wl.draw_dy(n, 1e-2, dtype, seed=910 + k)
+        b = {"x": gu.Buf(n * es).upload(x), "dy": gu.Buf(n * es).upload(dy)}
+        for name in ("y", "dx", "yd", "dxd"):
+            b[name] = gu.Buf(n * es)
+        b["c"], b["cd"], b["q"] = gu.Buf((n + 1) // 2), gu.Buf((n + 1) // 2), gu.Buf(4 * s2a.QSTATE_FLOATS)
+        jobs.append((dtype, n, x, dy, b))
+    torch.cuda.synchronize()
+    for rep in range(3):  # several rounds so that the two streams really overlap
+        for (dtype, n, x, dy, b), st in zip(jobs, streams):
+            s2a.act_fwd(b["x"].ptr, b["y"].ptr, b["c"].ptr, n, dtype, st.cuda_stream)
+            s2a.act_fwd_dyn(b["x"].ptr, b["yd"].ptr, b["cd"].ptr, b["q"].ptr, n, dtype, st.cuda_stream)
+        for (dtype, n, x, dy, b), st in zip(jobs, streams):
+            s2a.act_bwd(b["dy"].ptr, b["c"].ptr, b["dx"].ptr, n, dtype, st.cuda_stream)
+            s2a.act_bwd_dyn(b["dy"].ptr, b["cd"].ptr, b["q"].ptr, b["dxd"].ptr, n, dtype, st.cuda_stream)
+    torch.cuda.synchronize()
+    for dtype, n, x, dy, b in jobs:
+        y_ref, code_ref, packed_ref, near = oracle.fwd(x, dtype, band=parity.BAND)
+        packed = b["c"].download(np.uint8)
+        parity.check_codes(packed, code_ref, near, n)
+        parity.check_values(b["y"].download(gu.storage_np(dtype)), y_ref, dtype, "y")
+        differs = parity.unpack(packed, n) != code_ref
+        parity.check_values(b["dx"].download(gu.storage_np(dtype)), oracle.bwd(dy, dtype, packed_ref), dtype, "dx", skip=differs)
+        yd_ref, coded_ref, packedd_ref, neard, qmin, qscale = oracle.fwd_dyn(x, dtype, band=parity.BAND)
+        qs = b["q"].download(np.float32)
+        assert qs[2] == np.float32(qmin) and qs[3] == np.float32(qscale)
+        packedd = b["cd"].download(np.uint8)
+        parity.check_codes(packedd, coded_ref, neard, n)
+        differs = parity.unpack(packedd, n) != coded_ref
+        parity.check_values(b["dxd"].download(gu.storage_np(dtype)), oracle.bwd_dyn(dy, dtype, packedd_ref, qmin, qscale),
+                            dtype, "dx", skip=differs)
+        assert all(v.canaries_intact() for v in b.values())
+
+
 def test_outputs_are_fully_overwritten():
     """Stale 0xFF bytes in y / codes / dx never survive, including the pad nibble."""
     for dtype in DTYPES:
