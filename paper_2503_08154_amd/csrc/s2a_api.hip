@@ -243,6 +243,27 @@ void softmax_lds(int L, int* data_bytes, int* total_bytes)
     *total_bytes = *data_bytes + ((rpb * ((L + 1) / 2) + 15 + 15) / 16) * 16;
 }
 
+// Compute units of the current device (0 if the runtime does not say), looked up once per device.
+int device_units()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = -1;
+        cached[dev] = n;
+    }
+    return cached[dev] > 0 ? cached[dev] : 0;
+}
+// The staged kernels stagger their first round of blocks (see stagger_first_round) when the
+// launch has at least two rounds of kStaggerSlots blocks per compute unit.
+int stagger_units(int64_t blocks)
+{
+    const int units = device_units();
+    return units > 0 && blocks >= 2LL * s2a::kStaggerSlots * units ? units : 0;
+}
+
 // Calls f(std::integral_constant<int, SLOTS>) for SLOTS == slots.
 template <int G, int MAXS, int S = MAXS, typename F>
 void with_slots(int slots, F f)
@@ -260,10 +281,11 @@ int launch_softmax_fwd_staged(const void* x, void* y, uint8_t* codes, float* qp,
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     int data_bytes, total;
     softmax_lds<BF16, G>(L, &data_bytes, &total);
+    const int stagger = stagger_units(blocks);
     return checked_launch([&] {
         with_slots<G, pair_slots<BF16>()>(((L + 1) / 2 + G - 1) / G, [&](auto sc) {
             s2a::softmax_fwd_staged<BF16, G, decltype(sc)::value, kStagedBlock>
-                <<<dim3((unsigned)blocks), dim3(kStagedBlock), total, st>>>(x, y, codes, qp, rows, L, data_bytes);
+                <<<dim3((unsigned)blocks), dim3(kStagedBlock), total, st>>>(x, y, codes, qp, rows, L, data_bytes, stagger);
         });
     });
 }
@@ -276,10 +298,11 @@ int launch_softmax_bwd_staged(const void* dy, const uint8_t* codes, const float*
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     int data_bytes, total;
     softmax_lds<BF16, G>(L, &data_bytes, &total);
+    const int stagger = stagger_units(blocks);
     return checked_launch([&] {
         with_slots<G, pair_slots<BF16>()>(((L + 1) / 2 + G - 1) / G, [&](auto sc) {
             s2a::softmax_bwd_staged<BF16, G, decltype(sc)::value, kStagedBlock>
-                <<<dim3((unsigned)blocks), dim3(kStagedBlock), total, st>>>(dy, codes, qp, dx, rows, L, data_bytes);
+                <<<dim3((unsigned)blocks), dim3(kStagedBlock), total, st>>>(dy, codes, qp, dx, rows, L, data_bytes, stagger);
         });
     });
 }

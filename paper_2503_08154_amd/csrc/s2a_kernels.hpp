@@ -1040,12 +1040,33 @@ struct RowExp {
     }
 };
 
+// The blocks of a staged kernel live long (load the span, compute, store it) and
+// all of the first wave of blocks -- as many as fit the chip at once -- would
+// start together and move through the three phases in step: the memory system
+// is swamped, then idle while everyone computes, then swamped again, and with
+// only two to five such rounds per launch the blocks never drift apart.  So the
+// k-th block that a compute unit receives at the start of the launch (blocks
+// are handed out round-robin: k = blockIdx / compute units) first sleeps k
+// steps of 16 x 64 clocks (0.43 us; eight blocks per unit, up to 3 us).
+// Measured at the ViT-B/16 attention shape: 3-5 % on every kernel (steps of
+// 8 / 16 / 24 / 32 / 48: +2.5 / +3.5 / +1 / -1 / -5 % for the bf16 forward);
+// staggering neighbouring compute units instead of the slots of one unit: no
+// gain.  `stagger_units` is 0 for launches of less than two rounds.
+constexpr int kStaggerSlots = 8;
+__device__ __forceinline__ void stagger_first_round(int stagger_units)
+{
+    if (stagger_units > 0 && (int)blockIdx.x < kStaggerSlots * stagger_units) {
+        const int k = (int)blockIdx.x / stagger_units;
+        for (int q = 0; q < k; ++q) __builtin_amdgcn_s_sleep(16);
+    }
+}
+
 template <bool BF16, int G, int SLOTS, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void softmax_fwd_staged(const void* x, void* y,
                                                                     uint8_t* codes,
                                                                     float* __restrict__ qparams,
                                                                     int64_t rows, int L,
-                                                                    int data_bytes)
+                                                                    int data_bytes, int stagger_units)
 {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int RPB = BLOCK / G;           // rows per block
@@ -1063,6 +1084,7 @@ __global__ __launch_bounds__(BLOCK) void softmax_fwd_staged(const void* x, void*
     // lanes past the row end re-read the row's last element: a duplicate changes neither extreme
     const int o0 = ((has0 ? e0 : L - 1) - 2 * l) * ES, o1 = ((has1 ? e1 : L - 1) - 2 * l) * ES;
 
+    stagger_first_round(stagger_units);
     stage_in<ES, BLOCK>(x, lds, xa, xb, rows * L * ES);
     __syncthreads();
 
@@ -1153,7 +1175,7 @@ __global__ __launch_bounds__(BLOCK) void softmax_bwd_staged(const void* dy,
                                                                     const uint8_t* codes,
                                                                     const float* __restrict__ qparams,
                                                                     void* dx, int64_t rows, int L,
-                                                                    int data_bytes)
+                                                                    int data_bytes, int stagger_units)
 {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int RPB = BLOCK / G;
@@ -1172,6 +1194,7 @@ __global__ __launch_bounds__(BLOCK) void softmax_bwd_staged(const void* dy,
     const int o0 = ((has0 ? e0 : L - 1) - 2 * l) * ES, o1 = ((has1 ? e1 : L - 1) - 2 * l) * ES;
     const int oc = (has0 ? l + KL * G : rb - 1) - l;
 
+    stagger_first_round(stagger_units);
     stage_in<ES, BLOCK>(dy, lds, xa, xb, rows * L * ES);
     stage_in<1, BLOCK>(codes, lds + data_bytes, ca, cb, rows * rb);
     __syncthreads();
