@@ -124,8 +124,12 @@ int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int d
  *
  * Forward enqueues two kernels on `stream` (per-block min/max; the forward
  * kernel proper, which reduces those to the range and leaves the levels in
- * qstate) and reads x twice; both run for n == 0 as well.  No atomics are used,
- * so the result does not depend on scheduling.
+ * qstate); both run for n == 0 as well.  x is read twice, except that a
+ * wavefront of the first kernel stops reading once it has met a value at or
+ * beyond each clip limit (min = -2 and max = 2 are then settled), so tensors
+ * that exceed both limits throughout cost little more than the fixed-range
+ * entry point.  No atomics are used, so the result does not depend on
+ * scheduling.
  * Everything else is as for
  * s2a_act_fwd / s2a_act_bwd.  When the tensor has elements beyond both clip
  * limits the results equal the fixed-range entry points'.

@@ -166,6 +166,34 @@ def test_qstate_reused_by_a_smaller_tensor(dtype):
         assert bq.canaries_intact()
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("plant", ["same_wave_first_round", "different_waves", "later_round", "lower_only_everywhere"])
+def test_range_pass_stops_early_only_when_it_may(dtype, plant):
+    """A wave of the range pass stops reading once its first loads held a value at or beyond each
+    clip limit.  Narrow background with values beyond the limits planted where that shortcut does
+    and does not apply: the range is the oracle's in every case."""
+    n = 3_000_007
+    x64 = np.random.Generator(np.random.Philox(77)).uniform(-1.3, 0.9, n)
+    if plant == "same_wave_first_round":       # lanes 3 and 40 of the first wave of block 0
+        x64[3 * 8] = 5.0
+        x64[40 * 8 + 1] = -7.0
+    elif plant == "different_waves":           # no single wave sees both
+        x64[5] = 2.5
+        x64[n - 9] = -2.5
+    elif plant == "later_round":               # both in one wave's share, past its first loads
+        x64[100_000] = 3.0
+        x64[100_001] = -3.0
+    else:                                      # every wave meets the lower limit, none the upper
+        x64[::512] = -4.0
+    x = wl.to_storage(x64, dtype)
+    dy = wl.draw_dy(n, 1.0, dtype, seed=78)
+    _, _, _, qs = _check(x, dy, dtype)
+    if plant == "lower_only_everywhere":
+        assert qs[2] == -2.0 and qs[3] < np.float32(4.0 / 15.0)
+    else:
+        assert qs[2] == -2.0 and qs[3] == np.float32(4.0 / 15.0)
+
+
 @pytest.mark.parametrize("name", ["vit_b16", "vit_g14_f32"])
 def test_workload_full_size(name):
     """Full-size launch; the activations are scaled down so that no element reaches a
