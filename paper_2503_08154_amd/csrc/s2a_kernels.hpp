@@ -624,9 +624,10 @@ __global__ __launch_bounds__(kWave) void fwd_kernel(const u32x4* x, u32x4* y,
 
 // The same with the measured range (GELU only): qs holds the partial minima
 // and maxima of the range pass.  A wave that lies wholly inside the tensor (a
-// scalar branch) requests the partials, then its vector of x, and reduces the
-// partials while x is on its way.  The grid has at least one block, also for
-// n = 0, so that qs is always completed.
+// scalar branch) requests the first pair and its vector of x; if that pair
+// already is (-2, 2) the range is settled, otherwise the wave reads and
+// reduces all pairs.  The grid has at least one block, also for n = 0, so
+// that qs is always completed.
 template <bool BF16>
 __global__ __launch_bounds__(kWave) void fwd_dyn_kernel(const u32x4* x, u32x4* y,
                                                         uint8_t* __restrict__ codes,
@@ -636,20 +637,29 @@ __global__ __launch_bounds__(kWave) void fwd_dyn_kernel(const u32x4* x, u32x4* y
     constexpr int EPV = BF16 ? 8 : 4;
     const int64_t wave0 = (int64_t)blockIdx.x * kWave;
     const int64_t i = wave0 + threadIdx.x;
-    const RangeParts part = range_parts(qs);
     RangeBin r;
     if (wave0 + kWave <= nvec) {
+        // One block of the range pass that met both clip limits settles min = -2, max = 2 for the
+        // whole tensor: then the other 255 pairs need not be read (the constants are those the
+        // reduction would give: 15/4 and 1/2 + 2 * 15/4).
+        const float lo0 = qs[kQsPartMin], hi0 = qs[kQsPartMax];
         __builtin_amdgcn_s_setprio(3);
         u32x4 v = stream_load128(x + i);
         __builtin_amdgcn_s_setprio(0);
-        r = range_reduce(part);
+        if (lo0 == -2.0f && hi0 == 2.0f) {
+            r.bin = BinRange{3.75f, 8.0f};
+            r.lo = -2.0;
+            r.width = 4.0;
+        } else {
+            r = range_reduce(range_parts(qs));
+        }
         uint32_t c = fwd_vector<BF16, kActGelu>(v, r.bin);
         __builtin_amdgcn_s_setprio(3);
         stream_store128(y + i, v);
         store_codes<BF16>(codes, i, c);
         __builtin_amdgcn_s_setprio(0);
     } else {
-        r = range_reduce(part);
+        r = range_reduce(range_parts(qs));
         if (i < nvec) {
             u32x4 v = stream_load128(x + i);
             uint32_t c = fwd_vector<BF16, kActGelu>(v, r.bin);
