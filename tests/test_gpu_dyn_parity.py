@@ -100,10 +100,11 @@ def test_in_place(dtype, off):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind", ["narrow", "wide", "one_sided"])
 @pytest.mark.parametrize("off", [(1, 0), (0, 1), (3, 3)])
-def test_unaligned(dtype, off):
+def test_unaligned(dtype, off, kind):
     n = 8192 * 2 + 3
-    x = _draw(n, "narrow", dtype, seed=7)
+    x = _draw(n, kind, dtype, seed=7)
     dy = wl.draw_dy(n, 1e-2, dtype, seed=8)
     _check(x, dy, dtype, offset_elems=off[0], code_offset=off[1])
 
