@@ -83,9 +83,10 @@ def build_layers(torch, w: wl.Workload, distinct_seeds: bool):
 
 
 def run_step(layers, stream: int, ev=None, variant: str = "gelu"):
-    """fwd over all layers, then bwd in reverse; optional (e0, e1, e2) events around the phases.
+    """fwd over all layers, then bwd in reverse; optional (e0, e1, e2) events around the phases (e0
+    may be None: the phase then starts at the event that ended the step before).
     variant: "gelu" (the headline path), "gelu_dyn" (measured range) or "relu" (1-bit mask)."""
-    if ev:
+    if ev and ev[0] is not None:
         ev[0].record()
     for L in layers:
         if variant == "gelu_dyn":
@@ -112,22 +113,25 @@ def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds
     stream = torch.cuda.current_stream().cuda_stream
     for _ in range(warmup):
         run_step(layers, stream, variant=variant)
-    # the timed region of the whole-job figure: exactly `steps` steps between two synchronisations,
-    # nothing but the path's own launches on the stream
+    # the same steps once without anything but the path's own launches on the stream: what the
+    # events of the timed region cost (a record takes about 3 us on the stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
         run_step(layers, stream, variant=variant)
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    # the same steps again with events around the two phases, for the per-kernel durations (an event
-    # record costs about 3 us on the stream, 1-2 % of a step, which is why the region above has none)
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    wall_plain = time.perf_counter() - t0
+    # the timed region: exactly `steps` steps between two synchronisations, with an event after each
+    # phase (the forward phase of a step starts at the event that ended the step before)
+    events = [[None if k else torch.cuda.Event(enable_timing=True)] +
+              [torch.cuda.Event(enable_timing=True) for _ in range(2)] for k in range(steps)]
     t1 = time.perf_counter()
     for k in range(steps):
         run_step(layers, stream, events[k], variant=variant)
     torch.cuda.synchronize()
-    wall_events = time.perf_counter() - t1
+    wall = time.perf_counter() - t1
+    for k in range(1, steps):
+        events[k][0] = events[k - 1][2]
     fwd_steps = [e[0].elapsed_time(e[1]) for e in events]
     bwd_steps = [e[1].elapsed_time(e[2]) for e in events]
     fwd_ms, bwd_ms = sum(fwd_steps), sum(bwd_steps)
@@ -136,7 +140,7 @@ def time_workload(torch, w: wl.Workload, steps: int, warmup: int, distinct_seeds
     bytes_dir = sum(bytes_per_direction(L.n, L.dtype) for L in layers)
     res = {
         "ms_per_step": wall * 1e3 / steps,
-        "ms_per_step_with_phase_events": wall_events * 1e3 / steps,
+        "ms_per_step_without_events": wall_plain * 1e3 / steps,
         "elements_per_step": n_total,
         "bytes_per_step": 2 * bytes_dir,
         "launches_per_phase": len(layers),
@@ -428,7 +432,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(res["ms_per_step"], 4),
-        "ms_per_step_with_phase_events": round(res["ms_per_step_with_phase_events"], 4),
+        "ms_per_step_without_events": round(res["ms_per_step_without_events"], 4),
+        "value_without_events": round(res["bytes_per_step"] / (res["ms_per_step_without_events"] * 1e-3) / 1e9, 1),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
