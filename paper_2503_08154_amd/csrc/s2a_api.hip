@@ -244,6 +244,7 @@ void softmax_lds(int L, int* data_bytes, int* total_bytes)
 }
 
 // Compute units of the current device (0 if the runtime does not say), looked up once per device.
+// Threads that race on the first call store the same value.
 int device_units()
 {
     static int cached[64];
