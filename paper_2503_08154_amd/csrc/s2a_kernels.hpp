@@ -943,38 +943,81 @@ __device__ __forceinline__ void copy_unit(unsigned char* dst, const unsigned cha
     else if (UNIT == 2) *(uint16_t*)dst = *(const uint16_t*)src;
     else *dst = *src;
 }
+template <int UNIT, int BLOCK, int U>
+struct StageIn {
+    const unsigned char* g0;  // uniform over the block
+    unsigned char* lds;
+    int head, span, nv, nfull, i0;
+    bool cut;
+    u32x4 t[U];
+    __device__ __forceinline__ StageIn(const void* src, unsigned char* lds_, int64_t a, int64_t b, int64_t total)
+    {
+        const int64_t a_dn = a & ~(int64_t)15;
+        g0 = (const unsigned char*)src + a_dn;
+        lds = lds_;
+        head = (int)(a - a_dn);
+        span = (int)(b - a_dn);
+        nv = (span + 15) >> 4;
+        cut = a_dn + 16 * (int64_t)nv > total;  // the tensor ends inside the last vector
+        nfull = cut ? nv - 1 : nv;
+        // lane <-> vector mapping relative to a 256-byte aligned window, so that every
+        // wave-wide access covers whole, aligned lines except at the two ends of the span
+        i0 = (int)(((uintptr_t)g0 >> 4) & 15);
+    }
+    // One round = U loads per lane starting at vector `base`: request them, then (commit) put them into LDS.
+    __device__ __forceinline__ void issue(int base)
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = base + u * BLOCK + (int)threadIdx.x;
+            if (i >= 0 && i < nfull) t[u] = stream_load128((const u32x4*)(g0 + 16 * i));
+        }
+    }
+    __device__ __forceinline__ void commit(int base)
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = base + u * BLOCK + (int)threadIdx.x;
+            if (i >= 0 && i < nfull) *(u32x4*)(lds + 16 * i) = t[u];
+        }
+    }
+    // The rounds after the first, and the cut last vector.
+    __device__ __forceinline__ void finish()
+    {
+        for (int base = -i0 + U * BLOCK; base < nfull; base += U * BLOCK) {
+            issue(base);
+            commit(base);
+        }
+        const int tid = (int)threadIdx.x;
+        if (cut && tid < 16 / UNIT) {
+            const int p = 16 * (nv - 1) + tid * UNIT;
+            if (p >= head && p < span) copy_unit<UNIT>(lds + p, g0 + p);
+        }
+    }
+};
 template <int UNIT, int BLOCK>
 __device__ __forceinline__ void stage_in(const void* src, unsigned char* lds, int64_t a, int64_t b,
                                          int64_t total)
 {
-    const int64_t a_dn = a & ~(int64_t)15;
-    const unsigned char* g0 = (const unsigned char*)src + a_dn;  // uniform over the block
-    const int head = (int)(a - a_dn), span = (int)(b - a_dn);
-    const int nv = (span + 15) >> 4;
-    const bool cut = a_dn + 16 * (int64_t)nv > total;            // the tensor ends inside the last vector
-    const int nfull = cut ? nv - 1 : nv;
-    const int tid = (int)threadIdx.x;
-    // lane <-> vector mapping relative to a 256-byte aligned window, so that every
-    // wave-wide access covers whole, aligned lines except at the two ends of the span
-    const int i0 = (int)(((uintptr_t)g0 >> 4) & 15);
-    constexpr int U = 4;
-    for (int base = -i0; base < nfull; base += U * BLOCK) {
-        u32x4 t[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = base + u * BLOCK + tid;
-            if (i >= 0 && i < nfull) t[u] = stream_load128((const u32x4*)(g0 + 16 * i));
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = base + u * BLOCK + tid;
-            if (i >= 0 && i < nfull) *(u32x4*)(lds + 16 * i) = t[u];
-        }
-    }
-    if (cut && tid < 16 / UNIT) {
-        const int p = 16 * (nv - 1) + tid * UNIT;
-        if (p >= head && p < span) copy_unit<UNIT>(lds + p, g0 + p);
-    }
+    StageIn<UNIT, BLOCK, 4> st(src, lds, a, b, total);
+    st.issue(-st.i0);
+    st.commit(-st.i0);
+    st.finish();
+}
+// Two spans at once (the backward kernel's dL/dy and codes): the first round of both is requested
+// before either is waited for, so a block pays the memory latency once.
+template <int UNIT_A, int UNIT_B, int BLOCK>
+__device__ __forceinline__ void stage_in2(const void* src_a, unsigned char* lds_a, int64_t a0, int64_t a1, int64_t total_a,
+                                          const void* src_b, unsigned char* lds_b, int64_t b0, int64_t b1, int64_t total_b)
+{
+    StageIn<UNIT_A, BLOCK, 4> sa(src_a, lds_a, a0, a1, total_a);
+    StageIn<UNIT_B, BLOCK, 2> sb(src_b, lds_b, b0, b1, total_b);
+    sa.issue(-sa.i0);
+    sb.issue(-sb.i0);
+    sa.commit(-sa.i0);
+    sb.commit(-sb.i0);
+    sa.finish();
+    sb.finish();
 }
 // The reverse copy.  Vectors that lie wholly inside [a, b) are stored as such;
 // the ragged first and last vector belong partly to other blocks and are
@@ -1227,17 +1270,17 @@ __global__ __launch_bounds__(BLOCK) void softmax_bwd_staged(const void* dy,
     const int oc = (has0 ? l + KL * G : rb - 1) - l;
 
     stagger_first_round(stagger_units);
-    stage_in<ES, BLOCK>(dy, lds, xa, xb, rows * L * ES);
-    stage_in<1, BLOCK>(codes, lds + data_bytes, ca, cb, rows * rb);
-    __syncthreads();
-
     const int lrow = (int)threadIdx.x / G;
     const bool live = lrow < nrows;
     const int srow = live ? lrow : nrows - 1;
-    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + 2 * l) * ES;
-    const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + l;
+    // the row's (lo, scale) are requested before the staging loads, not after the barrier
     const float lo = qparams[2 * (row0 + srow)];
     const float scale = qparams[2 * (row0 + srow) + 1];
+    stage_in2<ES, 1, BLOCK>(dy, lds, xa, xb, rows * L * ES, codes, lds + data_bytes, ca, cb, rows * rb);
+    __syncthreads();
+
+    unsigned char* lx = lds + (int)(xa & 15) + (srow * L + 2 * l) * ES;
+    const unsigned char* lc = lds + data_bytes + (int)(ca & 15) + srow * rb + l;
 
     float ya[SLOTS], yb[SLOTS], ga[SLOTS], gb[SLOTS];
 #pragma unroll
