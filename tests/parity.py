@@ -10,6 +10,12 @@ Tolerances (stated by the benchmark spec, floors derived from the formats):
   dx     fp32: |err| <= 1e-5 * max(|dx_ref|, FLT_MIN);  bf16: <= 2 ulp
 Non-finite inputs are outside the tolerances: there only the kind of result
 (NaN / +inf / -inf) has to agree with the oracle.
+
+The oracle's in-band flags decide whether a code is compared bit-exactly or
+to +-1, so they are not taken on trust here: every caller also passes the set
+of elements that really lie inside the band, recounted with numpy from the
+inputs and the decision points (band_mask / level_band_mask), and check_codes
+fails if the oracle flags anything outside that set.
 """
 from __future__ import annotations
 
@@ -52,8 +58,47 @@ class CodeReport:
         return f"codes: n={self.n} in-band={self.flagged} differing={self.differing}"
 
 
-def check_codes(packed_gpu: np.ndarray, code_ref: np.ndarray, near: np.ndarray, n: int) -> CodeReport:
+GELU_POINTS = -2.0 + (np.arange(15) + 0.5) * (4.0 / 15.0)   # decision points of the fixed range
+SILU_POINTS = 1.702 * GELU_POINTS                            # the same under x -> x / 1.702
+
+
+def range_points(qmin: float, qscale: float) -> np.ndarray:
+    """Decision points of a measured range: min + (j + 1/2) * scale."""
+    return qmin + (np.arange(15) + 0.5) * qscale
+
+
+def band_mask(x64: np.ndarray, points: np.ndarray, band: float = BAND, clip: bool = False) -> np.ndarray:
+    """Elements within `band` (plus a rounding allowance) of a decision point.  clip=True judges
+    the value after the clip to [-2, 2] with NaN -> -2 (the measured-range variant)."""
+    v = x64
+    if clip:
+        v = np.where(np.isnan(x64), -2.0, np.clip(x64, -2.0, 2.0))
+    best = np.full(v.shape, np.inf)
+    with np.errstate(invalid="ignore"):
+        for p in points:
+            best = np.fmin(best, np.abs(v - p))
+    return best <= band * (1 + 1e-6) + 1e-15
+
+
+def level_band_mask(y_ref: np.ndarray, lo: np.ndarray, scale: np.ndarray, L: int, band_t: float) -> np.ndarray:
+    """Softmax: elements whose real-valued level index (y - lo)/scale is within band_t of k + 1/2."""
+    lo_e, s_e = np.repeat(lo, L), np.repeat(scale, L)
+    with np.errstate(invalid="ignore", divide="ignore"):
+        t = np.where(s_e > 0, (y_ref - lo_e) / s_e, 0.0)
+        return np.abs(t - np.floor(t) - 0.5) <= band_t * (1 + 1e-6) + 1e-9
+
+
+def check_flags(near: np.ndarray, allowed: np.ndarray):
+    """The oracle may flag only elements that the independent recount puts inside the band."""
+    wrong = (near != 0) & ~allowed
+    assert not wrong.any(), (f"the oracle flags {int(wrong.sum())} elements as in-band that are not "
+                             f"(first at {int(np.argmax(wrong))}); {int(allowed.sum())} really are")
+
+
+def check_codes(packed_gpu: np.ndarray, code_ref: np.ndarray, near: np.ndarray, n: int,
+                allowed: np.ndarray) -> CodeReport:
     assert packed_gpu.shape == ((n + 1) // 2,)
+    check_flags(near, allowed)
     got = unpack(packed_gpu, n)
     diff = got != code_ref
     # every differing nibble is in the band and off by one level

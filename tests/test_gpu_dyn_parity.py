@@ -71,7 +71,7 @@ def _check(x, dy, dtype, **kw):
     levels = np.array([oracle.gelu_deriv_approx(oracle.dequantize_dyn(k, qmin, qscale)) for k in range(16)])
     np.testing.assert_allclose(qs[16:32].astype(np.float64), levels, rtol=2e-7, atol=1e-12)
     finite = np.isfinite(wl.storage_to_f64(x, dtype))
-    rep = parity.check_codes(packed, code_ref, near, n)
+    rep = parity.check_codes(packed, code_ref, near, n, parity.band_mask(wl.storage_to_f64(x, dtype), parity.range_points(qmin, qscale), clip=True))
     wy = parity.check_values(y, y_ref, dtype, "y", finite_in=finite)
     dx_ref = oracle.bwd_dyn(dy, dtype, packed_ref, qmin, qscale)
     wdx = parity.check_values(dxs[1], dx_ref, dtype, "dx")          # oracle's codes in: every element
@@ -163,7 +163,7 @@ def test_qstate_reused_by_a_smaller_tensor(dtype):
         _, code_ref, _, near, qmin, qscale = oracle.fwd_dyn(x, dtype, band=parity.BAND)
         qs = bq.download(np.float32)
         assert qs[2] == np.float32(qmin) and qs[3] == np.float32(qscale), n
-        parity.check_codes(bc.download(np.uint8), code_ref, near, n)
+        parity.check_codes(bc.download(np.uint8), code_ref, near, n, parity.band_mask(wl.storage_to_f64(x, dtype), parity.range_points(qmin, qscale), clip=True))
         assert bq.canaries_intact()
 
 
@@ -218,7 +218,7 @@ def test_workload_full_size(name):
     qs = tq.cpu().numpy()
     assert qs[2] == np.float32(qmin) and qs[3] == np.float32(qscale) and qmin > -2.0
     packed = tc.cpu().numpy()
-    rep = parity.check_codes(packed, code_ref, near, n)
+    rep = parity.check_codes(packed, code_ref, near, n, parity.band_mask(wl.storage_to_f64(x, w.dtype), parity.range_points(qmin, qscale), clip=True))
     wy = parity.check_values(ty.cpu().numpy().view(gu.storage_np(w.dtype)), y_ref, w.dtype, "y")
     dx_ref = oracle.bwd_dyn(dy, w.dtype, packed_ref, qmin, qscale)
     differs = parity.unpack(packed, n) != code_ref

@@ -32,7 +32,7 @@ def _fwd_bwd_check(x, dy, dtype, report=None, **kw):
     y_ref, code_ref, packed_ref, near = oracle.fwd(x, dtype, band=parity.BAND)
     y, packed = gu.run_fwd(x, dtype, **kw)
     finite = np.isfinite(wl.storage_to_f64(x, dtype))
-    rep = parity.check_codes(packed, code_ref, near, n)
+    rep = parity.check_codes(packed, code_ref, near, n, parity.band_mask(wl.storage_to_f64(x, dtype), parity.GELU_POINTS))
     wy = parity.check_values(y, y_ref, dtype, "y", finite_in=finite)
     # backward in isolation: the oracle's codes in, every element checked
     dx_ref = oracle.bwd(dy, dtype, packed_ref)
@@ -93,7 +93,7 @@ def test_exhaustive_bf16_domain():
     y_ref, code_ref, packed_ref, near = oracle.fwd(bits, wl.BF16, band=parity.BAND)
     y, packed = gu.run_fwd(bits, wl.BF16)
     finite = np.isfinite(wl.bf16_bits_to_f32(bits))
-    rep = parity.check_codes(packed, code_ref, near, 65536)
+    rep = parity.check_codes(packed, code_ref, near, 65536, parity.band_mask(wl.storage_to_f64(bits, wl.BF16), parity.GELU_POINTS))
     parity.check_values(y, y_ref, wl.BF16, "y", finite_in=finite)
     print(f"\n[exhaustive bf16] {rep}")
     # non-finite x: NaN -> code 0, +inf -> 15, -inf -> 0 (checked above through the oracle's codes)
@@ -175,7 +175,7 @@ def test_two_streams_in_flight_together():
     for dtype, n, x, dy, b in jobs:
         y_ref, code_ref, packed_ref, near = oracle.fwd(x, dtype, band=parity.BAND)
         packed = b["c"].download(np.uint8)
-        parity.check_codes(packed, code_ref, near, n)
+        parity.check_codes(packed, code_ref, near, n, parity.band_mask(wl.storage_to_f64(x, dtype), parity.GELU_POINTS))
         parity.check_values(b["y"].download(gu.storage_np(dtype)), y_ref, dtype, "y")
         differs = parity.unpack(packed, n) != code_ref
         parity.check_values(b["dx"].download(gu.storage_np(dtype)), oracle.bwd(dy, dtype, packed_ref), dtype, "dx", skip=differs)
@@ -183,7 +183,8 @@ def test_two_streams_in_flight_together():
         qs = b["q"].download(np.float32)
         assert qs[2] == np.float32(qmin) and qs[3] == np.float32(qscale)
         packedd = b["cd"].download(np.uint8)
-        parity.check_codes(packedd, coded_ref, neard, n)
+        parity.check_codes(packedd, coded_ref, neard, n,
+                           parity.band_mask(wl.storage_to_f64(x, dtype), parity.range_points(qmin, qscale), clip=True))
         differs = parity.unpack(packedd, n) != coded_ref
         parity.check_values(b["dxd"].download(gu.storage_np(dtype)), oracle.bwd_dyn(dy, dtype, packedd_ref, qmin, qscale),
                             dtype, "dx", skip=differs)
@@ -201,7 +202,7 @@ def test_outputs_are_fully_overwritten():
             bc = gu.Buf((n + 1) // 2, fill=0xFF)
             s2a.act_fwd(bx.ptr, by.ptr, bc.ptr, n, dtype, torch.cuda.current_stream().cuda_stream)
             y_ref, code_ref, packed_ref, near = oracle.fwd(x, dtype, band=parity.BAND)
-            parity.check_codes(bc.download(np.uint8), code_ref, near, n)
+            parity.check_codes(bc.download(np.uint8), code_ref, near, n, parity.band_mask(wl.storage_to_f64(x, dtype), parity.GELU_POINTS))
             parity.check_values(by.download(gu.storage_np(dtype)), y_ref, dtype, "y")
 
 
@@ -228,7 +229,7 @@ def test_workload_full_size(name, layer, stage):
     packed = tc.cpu().numpy()
     del ty
     y_ref, code_ref, packed_ref, near = oracle.fwd(x, w.dtype, band=parity.BAND)
-    rep = parity.check_codes(packed, code_ref, near, n)
+    rep = parity.check_codes(packed, code_ref, near, n, parity.band_mask(wl.storage_to_f64(x, w.dtype), parity.GELU_POINTS))
     wy = parity.check_values(y, y_ref, w.dtype, "y")
     del y, y_ref
     tdy = torch.from_numpy(dy.view(np.uint8)).cuda()
@@ -282,6 +283,7 @@ def test_more_than_2_31_elements(dtype):
     parity.check_values(fetch(ty), y_ref, dtype, "y")
     code_s = np.concatenate([parity.unpack(tc[a // 2:(a + m + 1) // 2].cpu().numpy(), m) for a, m in spans])
     diff = code_s != code_ref
+    parity.check_flags(near, parity.band_mask(wl.storage_to_f64(x_s, dtype), parity.GELU_POINTS))
     assert not (diff & (near == 0)).any()
     assert (tc[-1:].cpu().numpy()[0] >> 4) == 0  # pad nibble of the odd-length tensor
     del ty

@@ -76,6 +76,7 @@ def _run_and_check(x, dy, dtype, rows, L, offset=0):
     # codes, row by row (each row starts on a byte)
     got = np.stack([parity.unpack(packed[r * rb:(r + 1) * rb], L) for r in range(rows)]).reshape(-1) if rows else np.empty(0, np.uint8)
     diff = (got != code_ref) & np.repeat(finite_rows, L)
+    parity.check_flags(near, parity.level_band_mask(y_ref, qmin, qscale, L, BAND_T[dtype]))
     assert not (diff & (near == 0)).any(), "a code differs outside the band"
     if diff.any():
         assert (np.abs(got[diff].astype(int) - code_ref[diff].astype(int)) == 1).all()
@@ -195,6 +196,7 @@ def test_in_place(dtype, L, offset):
     assert bx.canaries_intact() and bc.canaries_intact()
     parity.check_values(bx.download(gu.storage_np(dtype)), y_ref, dtype, "y")
     got = np.stack([parity.unpack(bc.download(np.uint8)[r * rb:(r + 1) * rb], L) for r in range(rows)]).reshape(-1)
+    parity.check_flags(near, parity.level_band_mask(y_ref, qmin, qscale, L, BAND_T[dtype]))
     assert not ((got != code_ref) & (near == 0)).any()
     qp32 = np.stack([qmin, qscale], axis=1).astype(np.float32)
     dx_ref = oracle.softmax_bwd(dy, dtype, packed_ref, qp32[:, 0].astype(np.float64), qp32[:, 1].astype(np.float64), rows, L)
@@ -240,6 +242,7 @@ def test_more_than_2_31_bytes():
         packed = tc[r0 * rb:(r0 + nr) * rb].cpu().numpy()
         got = np.stack([parity.unpack(packed[r * rb:(r + 1) * rb], L) for r in range(nr)]).reshape(-1)
         diff = got != code_ref
+        parity.check_flags(near, parity.level_band_mask(y_ref, qmin, qscale, L, BAND_T[dtype]))
         assert not (diff & (near == 0)).any(), f"rows from {r0}: a code differs outside the band"
         qp = tq[2 * r0:2 * (r0 + nr)].cpu().numpy().reshape(nr, 2)
         np.testing.assert_allclose(qp[:, 0], qmin, rtol=QP_RTOL[dtype], atol=1e-37)

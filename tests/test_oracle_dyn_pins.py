@@ -117,3 +117,72 @@ def test_degenerate_tensors(dtype):
     x = wl.to_storage(np.array([0.5, np.nan, 1.0]), dtype)
     _, code, _, _, qmin, qscale = oracle.fwd_dyn(x, dtype)
     assert qmin == -2.0 and code[1] == 0 and code[2] == 15
+
+
+def _in_band_exact(x32, lo: Fraction, scale: Fraction, band: Fraction):
+    """Which elements lie within `band` of a decision point lo + (j + 1/2) * scale, j = 0..14,
+    after the clip to [-2, 2]: exact rational arithmetic on the stored values."""
+    pts = [lo + (Fraction(2 * j + 1, 2)) * scale for j in range(15)]
+    out = []
+    for v in x32:
+        xc = min(max(Fraction(float(v)), Fraction(-2)), Fraction(2))
+        out.append(int(min(abs(xc - p) for p in pts) <= band))
+    return out
+
+
+def test_near_flag_marks_exactly_the_band_of_the_measured_range():
+    """Sec. 3.2, GeLU paragraph read literally: the decision points of Eq. 8 are
+    min + (j + 1/2) * scale of the clipped tensor.  Range [-1, 0.875] has scale 1/8, so every
+    decision point is a binary fraction and the hand-placed offsets are what they say."""
+    lo, hi = -1.0, 0.875
+    pts = [lo + (j + 0.5) * 0.125 for j in range(15)]
+    vals, want = [lo, hi], [0, 0]
+    for j in (0, 3, 7, 11, 14):
+        for off, flag in ((5e-7, 1), (-5e-7, 1), (2e-6, 0), (-2e-6, 0), (0.0, 1), (0.03, 0)):
+            vals.append(pts[j] + off)
+            want.append(flag)
+    x = np.array(vals, np.float32)
+    _, _, _, near, qmin, qscale = oracle.fwd_dyn(x, wl.F32, band=1e-6)
+    assert qmin == lo and qscale == 0.125
+    assert near.tolist() == want
+    assert near.tolist() == _in_band_exact(x, Fraction(lo), Fraction(1, 8), Fraction(1, 10 ** 6))
+    # a wider band takes in the +-2e-6 points as well, and nothing else
+    _, _, _, near3, _, _ = oracle.fwd_dyn(x, wl.F32, band=3e-6)
+    assert near3.tolist() == _in_band_exact(x, Fraction(lo), Fraction(1, 8), Fraction(3, 10 ** 6))
+    assert sum(near3.tolist()) == sum(want) + 10
+
+
+def test_near_flag_uses_the_clipped_value_and_the_measured_points():
+    """Values beyond a clip limit are judged where the clip puts them (the end of the range, half a
+    step from the nearest decision point), and the points move with the measured range: the same x
+    is in the band for one tensor and outside it for another."""
+    probe = np.float32(-0.9375)                                   # = -1 + 0.5 * 0.125
+    a = np.array([-1.0, 0.875, probe, 7.0, -9.0], np.float32)     # clips to [-2, 2]: range [-2, 2]
+    _, _, _, near_a, qmin, qscale = oracle.fwd_dyn(a, wl.F32, band=1e-6)
+    assert qmin == -2.0 and qscale == 4.0 / 15.0
+    assert near_a.tolist() == _in_band_exact(a, Fraction(-2), Fraction(4, 15), Fraction(1, 10 ** 6)) == [0, 0, 0, 0, 0]
+    b = np.array([-1.0, 0.875, probe], np.float32)                # range [-1, 0.875]
+    _, _, _, near_b, _, _ = oracle.fwd_dyn(b, wl.F32, band=1e-6)
+    assert near_b.tolist() == [0, 0, 1]
+    # a range so narrow that its upper end is within the band of the last decision point: a value
+    # far beyond the clip limit is flagged, because it is the clipped value 2 that is judged
+    c = np.array([2.0 - 3e-5, 7.0], np.float32)
+    _, _, _, near_c, qmin, qscale = oracle.fwd_dyn(c, wl.F32, band=1.5e-6)
+    lo = Fraction(float(c[0]))
+    assert near_c.tolist() == _in_band_exact(c, lo, (2 - lo) / 15, Fraction(15, 10 ** 7)) == [1, 1]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_near_flag_on_random_tensors_against_exact_rationals(dtype):
+    g = np.random.default_rng(12)
+    x = wl.to_storage(g.uniform(-1.25, 0.75, 3000), dtype)
+    band = 2e-3                                                   # wide enough to catch a few dozen draws
+    _, _, _, near, qmin, qscale = oracle.fwd_dyn(x, dtype, band=band)
+    xv = wl.storage_to_f64(x, dtype)
+    lo, hi = Fraction(float(xv.min())), Fraction(float(xv.max()))
+    want = np.array(_in_band_exact(xv, lo, (hi - lo) / 15, Fraction(band)))
+    # the oracle's scale is the rounded double of (hi - lo)/15: leave out the draws within 1e-12 of the band edge
+    pts = np.array([float(lo + Fraction(2 * j + 1, 2) * (hi - lo) / 15) for j in range(15)])
+    edge = np.abs(np.abs(xv[:, None] - pts[None, :]).min(axis=1) - band) < 1e-12
+    np.testing.assert_array_equal(near[~edge], want[~edge])
+    assert 20 < near.sum() < 0.2 * x.shape[0]

@@ -52,3 +52,35 @@ def test_array_passes(dtype):
     dx = oracle.silu_bwd(dy, dtype, packed)
     levels = np.array([oracle.silu_deriv_approx(oracle.silu_dequantize(k)) for k in range(16)])
     np.testing.assert_array_equal(dx, wl.storage_to_f64(dy, dtype) * levels[code])
+
+
+def test_near_flag_marks_exactly_the_band():
+    """The decision points of the SiLU quantizer are -3.404 + (j + 1/2) * 6.808/15 (the GELU
+    points times 1.702).  Hand-placed inputs either side of several of them, judged in exact
+    rational arithmetic on the stored fp32 values."""
+    from fractions import Fraction
+
+    clip, band = Fraction("3.404"), Fraction(1, 10 ** 6)
+    step = 2 * clip / 15
+    pts = [-clip + Fraction(2 * j + 1, 2) * step for j in range(15)]
+    vals, placed = [], []
+    for j in (0, 4, 7, 9, 14):
+        for off, flag in ((5e-7, 1), (-5e-7, 1), (2e-6, 0), (-2e-6, 0), (0.05, 0)):
+            vals.append(float(pts[j]) + off)
+            placed.append(flag)
+    vals += [0.0, 1e-7, -1e-5, 50.0, -50.0, 3.404, -3.404]
+    placed += [1, 1, 0, 0, 0, 0, 0]
+    x = np.array(vals, np.float32)
+    _, _, _, near = oracle.silu_fwd(x, wl.F32, band=1e-6)
+    exact = [int(min(abs(Fraction(float(v)) - p) for p in pts) <= band) for v in x]
+    assert near.tolist() == exact == placed
+    # scaled GELU points: a value is in the SiLU band exactly when value / 1.702 is in the
+    # GELU band of width band / 1.702 (the fixed-range flag has its own pin)
+    g = np.random.default_rng(5)
+    xs = g.uniform(-4.0, 4.0, 20000).astype(np.float32)
+    _, _, _, near_s = oracle.silu_fwd(xs, wl.F32, band=3e-3)
+    _, _, bounds = oracle.table()
+    dist = np.abs(xs.astype(np.float64)[:, None] - A * bounds[None, :]).min(axis=1)
+    sure = np.abs(dist - 3e-3) > 1e-9
+    np.testing.assert_array_equal(near_s[sure], (dist <= 3e-3)[sure].astype(np.uint8))
+    assert 100 < near_s.sum() < 2000

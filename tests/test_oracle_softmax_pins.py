@@ -146,3 +146,39 @@ def test_quantization_error_bound_on_the_gradient():
     yv = y.reshape(rows, L)
     bound = half * (dyv + (yv * dyv).sum(axis=1, keepdims=True)) + (yv + half) * (half * dyv).sum(axis=1, keepdims=True)
     assert np.all(np.abs(dx - xt.grad.numpy()) <= bound * (1 + 1e-9) + 1e-18)
+
+
+@pytest.mark.parametrize("band_t", [0.2, 0.05, 1e-3])
+def test_near_flag_marks_exactly_the_band_of_the_level_index(band_t):
+    """The softmax flag is on the real-valued level index t = (y - min y) / scale (Eq. 8): an
+    element is flagged when t is within band_t of k + 1/2.  Recomputed in exact rationals from the
+    oracle's own y (the flag is bookkeeping on y, not part of the method)."""
+    rows, L = 40, 197
+    x = _rows(rows, L, 2.0, 77)
+    y, code, _, qmin, qscale, near = oracle.softmax_fwd(x, wl.F32, rows, L, band_t=band_t)
+    y, near = y.reshape(rows, L), near.reshape(rows, L)
+    flagged = 0
+    for r in range(rows):
+        ys = [Fraction(float(v)) for v in y[r]]
+        lo, hi = min(ys), max(ys)
+        for i, v in enumerate(ys):
+            t = (v - lo) * 15 / (hi - lo)
+            d = abs(t - (t.numerator // t.denominator) - Fraction(1, 2))
+            if abs(float(d) - band_t) < 1e-9:      # the oracle forms t in doubles: skip the edge of the band
+                continue
+            assert near[r, i] == int(d <= Fraction(band_t)), (r, i, float(t))
+            flagged += int(near[r, i])
+    # most y of a row crowd near its minimum (t close to 0), so fewer than the uniform share
+    # 2 * band_t are flagged -- but some are, and far from all
+    assert 0.1 * 2 * band_t * rows * L < flagged < 2 * band_t * rows * L + 10
+
+
+def test_near_flag_hand_placed_row():
+    """A row of two extremes and probes whose y sit at known level indices: y proportional to
+    (1, 16) spans 15 steps of size 1 (in units of y_0), so an element with weight 1 + k + 1/2 + d has t = k + 1/2 + d."""
+    offs = [(0.0, 1), (4e-5, 1), (-4e-5, 1), (3e-4, 0), (-3e-4, 0), (0.25, 0)]
+    weights = [1.0, 16.0] + [1.0 + 6 + 0.5 + d for d, _ in offs]
+    x = np.log(np.array(weights)).astype(np.float32)
+    y, _, _, qmin, qscale, near = oracle.softmax_fwd(x, wl.F32, 1, len(weights), band_t=1e-4)
+    # fp32 rounding of log(w) moves t by at most ~16 * 2^-24 * |log w| * w ~ 3e-6: far inside the placements
+    assert near.tolist() == [0, 0] + [f for _, f in offs]
