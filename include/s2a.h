@@ -11,7 +11,10 @@
  * Conventions shared by every entry point
  *   - Returns an int: S2A_OK (0) or a negative S2A_ERR_* value.  Nothing
  *     throws, nothing blocks: kernels are enqueued on `stream` and the call
- *     returns.  Argument errors are detected on the host before any device
+ *     returns.  A call that launches resets the calling thread's HIP last-error
+ *     state first (as hipGetLastError does), so that S2A_ERR_LAUNCH reports this
+ *     launch only: an error left there by the caller's own earlier runtime calls
+ *     is dropped, not reported.  Argument errors are detected on the host before any device
  *     work, in the order NOT_INIT, DTYPE, SIZE, NULL, ALIGN.
  *   - x, y, dy, dx and codes are DEVICE pointers owned by the caller.  The
  *     library allocates no device memory and keeps no reference to them.
@@ -105,10 +108,9 @@ int s2a_act_bwd(const void* dy, const uint8_t* codes, void* dx, int64_t n, int d
                 void* stream);
 
 /*
- * Measured-range variant (GeLU paragraph read literally: after the clip, x is
- * "quantized between the maximal and minimal value" as in Eq. 8, i.e. min and
- * max are those of the clipped tensor; Eq. 9 then needs the same pair in the
- * backward pass).  One (min, scale) pair per call, kept beside the codes:
+ * Measured-range variant (GeLU paragraph read literally: Eq. 8's minimum and
+ * maximum are those of the clipped tensor rather than the clip limits; Eq. 9
+ * then needs the same pair in the backward pass).  One (min, scale) pair per call, kept beside the codes:
  *
  *   lo = min clip(x), hi = max clip(x), scale = (hi - lo) / 15
  *   code[i] = round((clip(x[i]) - lo) / scale)          (all 0 when hi == lo)
@@ -140,9 +142,8 @@ int s2a_act_bwd_dyn(const void* dy, const uint8_t* codes, const float* qstate, v
                     int dtype, void* stream);
 
 /*
- * SiLU / Swish with the same 4-bit scheme (GeLU paragraph, last sentence: the
- * design "is also effective for similar non-parametric functions, such as SiLU
- * and Swish"; the paper gives no constants).  SiLU(x) = x sigma(x) is the
+ * SiLU / Swish with the same 4-bit scheme (GeLU paragraph, last sentence, names
+ * both as covered by the design; the paper gives no constants for them).  SiLU(x) = x sigma(x) is the
  * paper's GELU form x sigma(1.702 x) under x -> x / 1.702, so everything
  * transfers by that substitution:
  *   forward   y = x * sigma(x);  code = round((clip(x, -3.404, 3.404) + 3.404) * 15 / 6.808)

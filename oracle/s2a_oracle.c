@@ -172,9 +172,8 @@ int s2a_oracle_bwd(const void *dy, int dtype, const uint8_t *packed, int64_t n, 
 }
 
 /* ------------------------------------------------------------------------
- * Data-dependent range ("between the maximal and minimal value", GeLU
- * paragraph read literally): Eq. 8's min and max are measured on the clipped
- * tensor instead of being the clip limits.  One (min, scale) pair per tensor,
+ * Data-dependent range (GeLU paragraph read literally): Eq. 8's min and max are
+ * measured on the clipped tensor instead of being the clip limits.  One (min, scale) pair per tensor,
  * stored beside the codes, as Eq. 9 needs both in the backward pass.
  *
  * Readings: the extremes are taken over the whole tensor (the paper names no
@@ -377,9 +376,8 @@ int s2a_oracle_softmax_bwd(const void *dy, int dtype, const uint8_t *packed, con
 }
 
 /* ------------------------------------------------------------------------
- * SiLU / Swish (GeLU paragraph, last sentence: the design also serves "similar
- * non-parametric functions, such as SiLU and Swish").  The paper gives no
- * constants for it.  SiLU(x) = x sigma(x) is Eq. 10 under x -> x / 1.702
+ * SiLU / Swish (the last sentence of the GeLU paragraph names both as served by
+ * the same design).  The paper gives no constants for them.  SiLU(x) = x sigma(x) is Eq. 10 under x -> x / 1.702
  * (SiLU(x) = 1.702 * GELU(x / 1.702)), so the derivative of SiLU at x is the
  * derivative of Eq. 10 at x / 1.702 and the paper's fit, range and bit width
  * carry over by that substitution: derivative sigma(x) + 0.22 sin(1.5 x/1.702),

@@ -2,6 +2,7 @@
 // checks, the quantization table, kernel selection and launch.  No device
 // memory is allocated and nothing synchronizes.
 #include "s2a.h"
+#include "s2a_bench.h"
 
 #include <math.h>
 

@@ -1,5 +1,5 @@
 """Host-side checks of the C ABI: the library loads without a GPU, exports every
-symbol include/s2a.h declares, and rejects bad arguments before touching a
+symbol include/*.h declares, and rejects bad arguments before touching a
 device.  No kernel is launched here."""
 import ctypes
 import os
@@ -15,7 +15,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "s2a.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(s2a_[a-z_]+)\s*\(", text)))
 
