@@ -230,17 +230,23 @@ int s2a_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float
                 int64_t batch, int64_t N, int64_t C, int r, int dtype, void* stream);
 
 /*
- * Measurement aid, not part of the method: a plain streaming copy of `nbytes`
- * bytes (a multiple of 16; src and dst device, 16-byte aligned, not
- * overlapping) with the same launch shape and the same load / store
- * instructions as the activation kernels -- one 16-byte vector per lane,
- * single-wave blocks.  The benchmark times it at the activation kernels'
- * traffic as the measured ceiling of this access pattern (Sec. 3.2 gives no
- * kernel design; this is what the HBM system sustains for read-once,
- * write-once streams).  S2A_ERR_SIZE if nbytes is negative or not a multiple
- * of 16, S2A_ERR_ALIGN for misaligned pointers.
+ * s2a_lrp_bwd for callers that cannot provide working memory because they cannot
+ * allocate any: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * s2a_lrp_bwd, without `work`: the N*C floats between the two kernels live in
+ * a fixed array inside the library's device code (S2A_LRP_NOALLOC_MAX_FLOATS
+ * floats = 4 MiB, held on every GPU the library runs on until the process
+ * ends).  The call allocates nothing and calls no allocating routine; the first
+ * call on a device only looks up the array's address on that device.
+ *   - N*C > S2A_LRP_NOALLOC_MAX_FLOATS returns S2A_ERR_SIZE (use s2a_lrp_bwd).
+ *   - All calls on one GPU share the array: calls that may overlap there (two
+ *     streams, two threads) race on it and must be ordered by the caller.
+ *     Nothing in it has to start at zero, and it keeps the last call's contents.
+ *   - S2A_ERR_LAUNCH also reports that the array's address could not be found.
  */
-int s2a_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream);
+#define S2A_LRP_NOALLOC_MAX_FLOATS (1 << 20)
+int s2a_lrp_bwd_noalloc(const void* dy, const float* A, const float* B, float* dA, float* dB,
+                        int64_t batch, int64_t N, int64_t C, int r, int dtype, void* stream);
 
 /* Static, NUL-terminated description of a return code.  Never NULL. */
 const char* s2a_strerror(int code);

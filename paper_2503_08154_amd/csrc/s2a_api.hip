@@ -6,9 +6,16 @@
 
 #include <math.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "s2a_kernels.hpp"
+
+// Library-owned working memory for s2a_lrp_bwd_noalloc: part of the loaded code object, so every
+// GPU the library runs on holds its own copy (4 MiB) at its own address until the process ends.
+// In host code the name below is only a handle for hipGetSymbolAddress, never an address:
+// kernels receive the looked-up pointer (scratch_on_current_device).
+static __device__ __align__(256) float scratch[S2A_LRP_NOALLOC_MAX_FLOATS];
 
 namespace {
 
@@ -453,6 +460,60 @@ int check_lrp(int64_t batch, int64_t N, int64_t C, int r, int dtype)
 
 static_assert(s2a::kQsFloats == S2A_QSTATE_FLOATS, "header and kernels disagree on the qstate size");
 
+// Both kernels of the Low-Rank-Prompt backward pass; `work` holds N*C floats (the batch-summed
+// gradient between the two).  Arguments are checked by the callers.
+int launch_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float* dB, float* work,
+                   int64_t batch, int64_t N, int64_t C, int r, int dtype, hipStream_t st)
+{
+    // LDS of the first kernel: S partial rows and the summed row of one chunk of channels
+    const int epv = dtype == S2A_BF16 ? 8 : 4;
+    const int64_t vpt = C / epv;
+    const int64_t cv = vpt < s2a::kLrpTokenBlock ? vpt : s2a::kLrpTokenBlock;
+    const size_t lds = (size_t)((s2a::kLrpTokenBlock / cv) * cv + cv) * epv * sizeof(float);
+    int rc = checked_launch([&] {
+        if (dtype == S2A_BF16)
+            s2a::lrp_grad_token_kernel<true><<<dim3((unsigned)N), dim3(s2a::kLrpTokenBlock), lds, st>>>(
+                (const s2a::u32x4*)dy, B, work, dA, (int)batch, (int)N, (int)C, r);
+        else
+            s2a::lrp_grad_token_kernel<false><<<dim3((unsigned)N), dim3(s2a::kLrpTokenBlock), lds, st>>>(
+                (const s2a::u32x4*)dy, B, work, dA, (int)batch, (int)N, (int)C, r);
+    });
+    if (rc != S2A_OK) return rc;
+    return checked_launch([&] {
+        s2a::lrp_grad_b_kernel<<<dim3((unsigned)((C + s2a::kWave - 1) / s2a::kWave), (unsigned)r),
+                                 dim3(s2a::kLrpGradBBlock), 0, st>>>(work, A, dB, (int)N, (int)C, r);
+    });
+}
+
+int check_lrp_bwd_ptrs(const void* dy, const float* A, const float* B, float* dA, float* dB, int64_t batch)
+{
+    if ((batch > 0 && !dy) || !A || !B || !dA || !dB) return S2A_ERR_NULL;
+    if (!aligned(dy, 16) || !aligned(A, 4) || !aligned(B, 4) || !aligned(dA, 4) || !aligned(dB, 4))
+        return S2A_ERR_ALIGN;
+    return S2A_OK;
+}
+
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices];   // per device, looked up on the first call with that device current
+std::mutex g_scratch_mutex;
+
+// The device address of `scratch` on the current device; nullptr if the runtime cannot say.
+float* scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = (float*)p;
+    }
+    return g_scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -625,29 +686,25 @@ int s2a_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float
     int rc = check_lrp(batch, N, C, r, dtype);
     if (rc != S2A_OK) return rc;
     if (N == 0 || C == 0) return S2A_OK;
-    if ((batch > 0 && !dy) || !A || !B || !dA || !dB || !work) return S2A_ERR_NULL;
-    if (!aligned(dy, 16) || !aligned(A, 4) || !aligned(B, 4) || !aligned(dA, 4) || !aligned(dB, 4) || !aligned(work, 4))
-        return S2A_ERR_ALIGN;
-    if (N > 0x7fffffff) return S2A_ERR_SIZE;
-    hipStream_t st = (hipStream_t)stream;
-    // LDS of the first kernel: S partial rows and the summed row of one chunk of channels
-    const int epv = dtype == S2A_BF16 ? 8 : 4;
-    const int64_t vpt = C / epv;
-    const int64_t cv = vpt < s2a::kLrpTokenBlock ? vpt : s2a::kLrpTokenBlock;
-    const size_t lds = (size_t)((s2a::kLrpTokenBlock / cv) * cv + cv) * epv * sizeof(float);
-    rc = checked_launch([&] {
-        if (dtype == S2A_BF16)
-            s2a::lrp_grad_token_kernel<true><<<dim3((unsigned)N), dim3(s2a::kLrpTokenBlock), lds, st>>>(
-                (const s2a::u32x4*)dy, B, work, dA, (int)batch, (int)N, (int)C, r);
-        else
-            s2a::lrp_grad_token_kernel<false><<<dim3((unsigned)N), dim3(s2a::kLrpTokenBlock), lds, st>>>(
-                (const s2a::u32x4*)dy, B, work, dA, (int)batch, (int)N, (int)C, r);
-    });
+    rc = check_lrp_bwd_ptrs(dy, A, B, dA, dB, batch);
     if (rc != S2A_OK) return rc;
-    return checked_launch([&] {
-        s2a::lrp_grad_b_kernel<<<dim3((unsigned)((C + s2a::kWave - 1) / s2a::kWave), (unsigned)r),
-                                 dim3(s2a::kLrpGradBBlock), 0, st>>>(work, A, dB, (int)N, (int)C, r);
-    });
+    if (!work) return S2A_ERR_NULL;
+    if (!aligned(work, 4)) return S2A_ERR_ALIGN;
+    return launch_lrp_bwd(dy, A, B, dA, dB, work, batch, N, C, r, dtype, (hipStream_t)stream);
+}
+
+int s2a_lrp_bwd_noalloc(const void* dy, const float* A, const float* B, float* dA, float* dB,
+                        int64_t batch, int64_t N, int64_t C, int r, int dtype, void* stream)
+{
+    int rc = check_lrp(batch, N, C, r, dtype);
+    if (rc != S2A_OK) return rc;
+    if (N * C > (int64_t)S2A_LRP_NOALLOC_MAX_FLOATS) return S2A_ERR_SIZE;  // beyond the library's working memory
+    if (N == 0 || C == 0) return S2A_OK;
+    rc = check_lrp_bwd_ptrs(dy, A, B, dA, dB, batch);
+    if (rc != S2A_OK) return rc;
+    float* work = scratch_on_current_device();
+    if (!work) return S2A_ERR_LAUNCH;
+    return launch_lrp_bwd(dy, A, B, dA, dB, work, batch, N, C, r, dtype, (hipStream_t)stream);
 }
 
 int s2a_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream)

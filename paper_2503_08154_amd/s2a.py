@@ -24,11 +24,12 @@ ERR_LAUNCH = -6
 ERR_ALIGN = -7
 QSTATE_FLOATS = 544
 SOFTMAX_MAX_L = 1024
+LRP_NOALLOC_MAX_FLOATS = 1 << 20
 
 EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd",
            "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_silu_fwd", "s2a_silu_bwd", "s2a_relu_fwd", "s2a_relu_bwd",
            "s2a_softmax_fwd", "s2a_softmax_bwd", "s2a_cap_fwd", "s2a_cap_bwd",
-           "s2a_lrp_fwd", "s2a_lrp_bwd", "s2a_stream_copy", "s2a_strerror")
+           "s2a_lrp_fwd", "s2a_lrp_bwd", "s2a_lrp_bwd_noalloc", "s2a_stream_copy", "s2a_strerror")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libs2a.so")
 _lib = None
@@ -82,6 +83,8 @@ def lib() -> ctypes.CDLL:
         l.s2a_lrp_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i, i, vp]
         l.s2a_lrp_bwd.restype = i
         l.s2a_lrp_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i, i, vp]
+        l.s2a_lrp_bwd_noalloc.restype = i
+        l.s2a_lrp_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i, i, vp]
         l.s2a_stream_copy.restype = i
         l.s2a_stream_copy.argtypes = [vp, vp, i64, vp]
         l.s2a_strerror.restype = ctypes.c_char_p
@@ -213,6 +216,14 @@ def lrp_bwd(dy: int, A: int, B: int, dA: int, dB: int, work: int, batch: int, N:
     rc = lib().s2a_lrp_bwd(dy, A, B, dA, dB, work, int(batch), int(N), int(C), int(r), int(dtype), stream)
     if check and rc != OK:
         raise S2AError(rc, "s2a_lrp_bwd")
+    return rc
+
+
+def lrp_bwd_noalloc(dy: int, A: int, B: int, dA: int, dB: int, batch: int, N: int, C: int, r: int,
+                    dtype: int, stream: int = 0, check: bool = True) -> int:
+    rc = lib().s2a_lrp_bwd_noalloc(dy, A, B, dA, dB, int(batch), int(N), int(C), int(r), int(dtype), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_lrp_bwd_noalloc")
     return rc
 
 
