@@ -22,6 +22,20 @@ extern "C" {
  */
 int s2a_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream);
 
+/*
+ * The same copy with the traffic shape of an activation kernel: besides the 16
+ * bytes a lane moves from src to dst, it moves `side_bytes` (4 or 2: the packed
+ * codes of 8 bf16 or 4 fp32 elements) to or from `side`, with the load / store
+ * instructions the activation kernels use for their codes.
+ *   side_is_input == 0   forward shape: src read, dst and side written
+ *   side_is_input != 0   backward shape: src and side read, dst written
+ * `side` holds nbytes/16 * side_bytes bytes, 4-byte aligned.  The benchmark times
+ * it at an activation kernel's size as the measured ceiling of that kernel's
+ * access pattern.  S2A_ERR_SIZE also for a side_bytes other than 2 or 4.
+ */
+int s2a_stream_copy_shaped(const void* src, void* dst, void* side, int64_t nbytes, int side_bytes,
+                           int side_is_input, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

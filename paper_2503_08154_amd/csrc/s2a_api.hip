@@ -129,9 +129,15 @@ int launch_bwd(const void* dy, const uint8_t* codes, void* dx, const float* qs, 
         int64_t nvec;
         unsigned blocks;
         if (!vector_grid<BF16>(n, &nvec, &blocks)) return S2A_ERR_SIZE;
+        // codes that are 16-byte aligned (not only 4) are fetched a wave at a time
+        const bool wave_codes = aligned(codes, 16);
         return checked_launch([&] {
-            s2a::bwd_kernel<BF16, DYN><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
-                (const s2a::u32x4*)dy, codes, (s2a::u32x4*)dx, table, qs, n, nvec);
+            if (wave_codes)
+                s2a::bwd_kernel<BF16, DYN, true><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+                    (const s2a::u32x4*)dy, codes, (s2a::u32x4*)dx, table, qs, n, nvec);
+            else
+                s2a::bwd_kernel<BF16, DYN, false><<<dim3(blocks), dim3(s2a::kWave), 0, st>>>(
+                    (const s2a::u32x4*)dy, codes, (s2a::u32x4*)dx, table, qs, n, nvec);
         });
     }
     return checked_launch([&] {
@@ -719,6 +725,29 @@ int s2a_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream)
     return checked_launch([&] {
         s2a::stream_copy_kernel<<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, (hipStream_t)stream>>>(
             (const s2a::u32x4*)src, (s2a::u32x4*)dst, nvec);
+    });
+}
+
+int s2a_stream_copy_shaped(const void* src, void* dst, void* side, int64_t nbytes, int side_bytes,
+                           int side_is_input, void* stream)
+{
+    if (nbytes < 0 || nbytes % 16 != 0 || (side_bytes != 2 && side_bytes != 4)) return S2A_ERR_SIZE;
+    if (nbytes == 0) return S2A_OK;
+    if (!src || !dst || !side) return S2A_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(dst, 16) || !aligned(side, 4)) return S2A_ERR_ALIGN;
+    const int64_t nvec = nbytes / 16;
+    const int64_t blocks = (nvec + s2a::kWave - 1) / s2a::kWave;
+    if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    const dim3 grid((unsigned)blocks), block(s2a::kWave);
+    hipStream_t st = (hipStream_t)stream;
+    const s2a::u32x4* s = (const s2a::u32x4*)src;
+    s2a::u32x4* d = (s2a::u32x4*)dst;
+    uint8_t* c = (uint8_t*)side;
+    return checked_launch([&] {
+        if (side_bytes == 4 && side_is_input) s2a::stream_copy_shaped_kernel<4, true><<<grid, block, 0, st>>>(s, d, c, nvec);
+        else if (side_bytes == 4) s2a::stream_copy_shaped_kernel<4, false><<<grid, block, 0, st>>>(s, d, c, nvec);
+        else if (side_is_input) s2a::stream_copy_shaped_kernel<2, true><<<grid, block, 0, st>>>(s, d, c, nvec);
+        else s2a::stream_copy_shaped_kernel<2, false><<<grid, block, 0, st>>>(s, d, c, nvec);
     });
 }
 

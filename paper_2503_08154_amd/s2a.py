@@ -29,7 +29,8 @@ LRP_NOALLOC_MAX_FLOATS = 1 << 20
 EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd",
            "s2a_act_fwd_dyn", "s2a_act_bwd_dyn", "s2a_silu_fwd", "s2a_silu_bwd", "s2a_relu_fwd", "s2a_relu_bwd",
            "s2a_softmax_fwd", "s2a_softmax_bwd", "s2a_cap_fwd", "s2a_cap_bwd",
-           "s2a_lrp_fwd", "s2a_lrp_bwd", "s2a_lrp_bwd_noalloc", "s2a_stream_copy", "s2a_strerror")
+           "s2a_lrp_fwd", "s2a_lrp_bwd", "s2a_lrp_bwd_noalloc", "s2a_stream_copy", "s2a_stream_copy_shaped",
+           "s2a_strerror")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libs2a.so")
 _lib = None
@@ -87,6 +88,8 @@ def lib() -> ctypes.CDLL:
         l.s2a_lrp_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i, i, vp]
         l.s2a_stream_copy.restype = i
         l.s2a_stream_copy.argtypes = [vp, vp, i64, vp]
+        l.s2a_stream_copy_shaped.restype = i
+        l.s2a_stream_copy_shaped.argtypes = [vp, vp, vp, i64, i, i, vp]
         l.s2a_strerror.restype = ctypes.c_char_p
         l.s2a_strerror.argtypes = [i]
         _lib = l
@@ -231,4 +234,12 @@ def stream_copy(src: int, dst: int, nbytes: int, stream: int = 0, check: bool = 
     rc = lib().s2a_stream_copy(src, dst, int(nbytes), stream)
     if check and rc != OK:
         raise S2AError(rc, "s2a_stream_copy")
+    return rc
+
+
+def stream_copy_shaped(src: int, dst: int, side: int, nbytes: int, side_bytes: int, side_is_input: int,
+                       stream: int = 0, check: bool = True) -> int:
+    rc = lib().s2a_stream_copy_shaped(src, dst, side, int(nbytes), int(side_bytes), int(side_is_input), stream)
+    if check and rc != OK:
+        raise S2AError(rc, "s2a_stream_copy_shaped")
     return rc
