@@ -296,13 +296,23 @@ def roofline_of(res, w: wl.Workload, traffic, ceilings=None):
 
 # ---------------------------------------------------------------- rows beyond the headline path ----
 
+WARM_MS = 40.0  # the rows beyond the headline path warm up by time: see time_ops
+
+
 def time_ops(torch, ops, sets: int, steps: int, warmup: int):
-    """ops: {name: fn(set_index)}; each timed alone over `sets` buffer sets, `steps` times."""
+    """ops: {name: fn(set_index)}; each timed alone over `sets` buffer sets, `steps` times, after
+    `warmup` passes over the sets and at least WARM_MS of the same launches: the clocks take tens of
+    milliseconds to settle after an idle period, and the kernels with real arithmetic (softmax: 26.5 us
+    after 2 ms of warm-up, 23.5 us after 50 ms or 300 ms) show it far more than the streaming ones."""
     out = {}
     for name, fn in ops.items():
-        for _ in range(warmup):
+        t0 = time.perf_counter()
+        k = 0
+        while k < warmup or (time.perf_counter() - t0) * 1e3 < WARM_MS:
             for i in range(sets):
                 fn(i)
+            torch.cuda.synchronize()
+            k += 1
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()

@@ -1246,10 +1246,12 @@ __global__ __launch_bounds__(BLOCK) void softmax_fwd_staged(const void* x, void*
     }
 
     // pass 3: y and the codes into LDS.  lo <= y <= hi and inv_scale is
-    // 15/(hi - lo) to 1 ulp, so (y - lo)*inv_scale + 0.5 stays below 15.5*(1 + 2^-22):
-    // the saturating conversion (floor; NaN and negatives -> 0) never exceeds 15.
+    // 15/(hi - lo) to 1 ulp, so (y - lo)*inv_scale + 0.5 stays below 15.5*(1 + 2^-21):
+    // the saturating conversion (floor; NaN and negatives -> 0) never exceeds 15.  The
+    // offset 0.5 - lo*inv_scale is formed once per row, so a code costs one FMA and one convert.
+    const float q_off = __builtin_fmaf(-lo, inv_scale, 0.5f);
     auto quantize = [&](float yk) -> uint32_t {
-        float t = __builtin_fmaf(yk - lo, inv_scale, 0.5f);
+        float t = __builtin_fmaf(yk, inv_scale, q_off);
         uint32_t c;
         asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));
         return c;
