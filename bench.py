@@ -401,7 +401,7 @@ def cap_lrp_row(torch, row: str, batch: int, N: int, C: int, steps: int, warmup:
     nbytes = {"cap_fwd": 2 * n + 2 * n // r_cap, "cap_bwd": 2 * n + 2 * n // r_cap, "lrp_fwd": 4 * n,
               "lrp_bwd": 2 * n + 4 * (2 * N * C + 2 * (N * rank + rank * C))}
     kernels = {"cap_fwd": "s2a::cap_fwd_kernel<bf16, 8>", "cap_bwd": "s2a::cap_bwd_kernel<bf16, 8>",
-               "lrp_fwd": "s2a::lrp_fwd_kernel<bf16>", "lrp_bwd": "s2a::lrp_grad_token_kernel<bf16> + s2a::lrp_grad_b_kernel"}
+               "lrp_fwd": "s2a::lrp_fwd_kernel<bf16>", "lrp_bwd": "s2a::lrp_batch_sum_kernel<bf16> + s2a::lrp_grad_ab_kernel"}
     us = time_ops(torch, ops, sets, steps, warmup)
     del bufs
     torch.cuda.empty_cache()

@@ -220,9 +220,10 @@ int s2a_cap_bwd(const void* dy, void* dx, int64_t n_out, int r, int dtype, void*
  *   A, dA     device, fp32 [N x r] row-major;  B, dB  device, fp32 [r x C]
  *   work      device, N*C floats of scratch owned by the caller (holds the
  *             batch-summed gradient between the kernels of one call)
- *   r         1..64 (the paper uses 30); C a multiple of 8 (bf16) or 4 (fp32),
- *             else S2A_ERR_SIZE
- * Forward is one kernel; backward enqueues two.  Needs no s2a_qtable_init.
+ *   r         1..128 (the paper uses 30 and scales it up to 100, Sec. 4.3); C a
+ *             multiple of 8 (bf16) or 4 (fp32), else S2A_ERR_SIZE
+ * Forward is one kernel; backward enqueues two (the batch sum of dL/dy into
+ * `work`, then both products).  Needs no s2a_qtable_init.
  */
 int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t batch, int64_t N,
                 int64_t C, int r, int dtype, void* stream);

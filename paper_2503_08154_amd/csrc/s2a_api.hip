@@ -471,23 +471,27 @@ static_assert(s2a::kQsFloats == S2A_QSTATE_FLOATS, "header and kernels disagree 
 int launch_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, float* dB, float* work,
                    int64_t batch, int64_t N, int64_t C, int r, int dtype, hipStream_t st)
 {
-    // LDS of the first kernel: S partial rows and the summed row of one chunk of channels
     const int epv = dtype == S2A_BF16 ? 8 : 4;
-    const int64_t vpt = C / epv;
-    const int64_t cv = vpt < s2a::kLrpTokenBlock ? vpt : s2a::kLrpTokenBlock;
-    const size_t lds = (size_t)((s2a::kLrpTokenBlock / cv) * cv + cv) * epv * sizeof(float);
+    const int64_t sample = N * (C / epv);  // vectors per sample
+    const int64_t sum_blocks = (sample + s2a::kLrpSumPos - 1) / s2a::kLrpSumPos;
+    // tokens (dA) and 32-channel slabs (dB) in whole groups of 8, one member per XCD
+    const int64_t x = s2a::kXcds;
+    const int64_t blocks_a = (N + x - 1) / x * x * ((r + s2a::kLrpDaRanks - 1) / s2a::kLrpDaRanks);
+    const int64_t slabs = (C + s2a::kLrpDbChannels - 1) / s2a::kLrpDbChannels;
+    const int64_t blocks_b = (slabs + x - 1) / x * x * ((r + s2a::kLrpRankTile - 1) / s2a::kLrpRankTile);
+    if (sum_blocks > 0x7fffffffLL || blocks_a + blocks_b > 0x7fffffffLL) return S2A_ERR_SIZE;
     int rc = checked_launch([&] {
         if (dtype == S2A_BF16)
-            s2a::lrp_grad_token_kernel<true><<<dim3((unsigned)N), dim3(s2a::kLrpTokenBlock), lds, st>>>(
-                (const s2a::u32x4*)dy, B, work, dA, (int)batch, (int)N, (int)C, r);
+            s2a::lrp_batch_sum_kernel<true><<<dim3((unsigned)sum_blocks), dim3(s2a::kLrpSumBlock), 0, st>>>(
+                (const s2a::u32x4*)dy, work, (int)batch, sample);
         else
-            s2a::lrp_grad_token_kernel<false><<<dim3((unsigned)N), dim3(s2a::kLrpTokenBlock), lds, st>>>(
-                (const s2a::u32x4*)dy, B, work, dA, (int)batch, (int)N, (int)C, r);
+            s2a::lrp_batch_sum_kernel<false><<<dim3((unsigned)sum_blocks), dim3(s2a::kLrpSumBlock), 0, st>>>(
+                (const s2a::u32x4*)dy, work, (int)batch, sample);
     });
     if (rc != S2A_OK) return rc;
     return checked_launch([&] {
-        s2a::lrp_grad_b_kernel<<<dim3((unsigned)((C + s2a::kWave - 1) / s2a::kWave), (unsigned)r),
-                                 dim3(s2a::kLrpGradBBlock), 0, st>>>(work, A, dB, (int)N, (int)C, r);
+        s2a::lrp_grad_ab_kernel<<<dim3((unsigned)(blocks_a + blocks_b)), dim3(s2a::kLrpAbBlock), 0, st>>>(
+            work, A, B, dA, dB, (int)N, (int)C, r, (int)blocks_b);
     });
 }
 
@@ -676,13 +680,15 @@ int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t 
     const int64_t sample = N * (C / epv);               // vectors per sample
     const int64_t blocks = (sample + s2a::kLrpPos - 1) / s2a::kLrpPos;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
+    const dim3 grid((unsigned)blocks), block(s2a::kLrpFwdBlock);
+    const s2a::u32x4* xv = (const s2a::u32x4*)x;
+    s2a::u32x4* yv = (s2a::u32x4*)y;
+    const bool two = r > 64;  // rounds of 64 ranks in the kernel's prompt sum
     return checked_launch([&] {
-        if (dtype == S2A_BF16)
-            s2a::lrp_fwd_kernel<true><<<dim3((unsigned)blocks), dim3(s2a::kLrpFwdBlock), 0, st>>>(
-                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r);
-        else
-            s2a::lrp_fwd_kernel<false><<<dim3((unsigned)blocks), dim3(s2a::kLrpFwdBlock), 0, st>>>(
-                (const s2a::u32x4*)x, (s2a::u32x4*)y, A, B, (int)batch, (int)N, (int)C, r);
+        if (dtype == S2A_BF16 && !two) s2a::lrp_fwd_kernel<true, 1><<<grid, block, 0, st>>>(xv, yv, A, B, (int)batch, (int)N, (int)C, r);
+        else if (dtype == S2A_BF16) s2a::lrp_fwd_kernel<true, 2><<<grid, block, 0, st>>>(xv, yv, A, B, (int)batch, (int)N, (int)C, r);
+        else if (!two) s2a::lrp_fwd_kernel<false, 1><<<grid, block, 0, st>>>(xv, yv, A, B, (int)batch, (int)N, (int)C, r);
+        else s2a::lrp_fwd_kernel<false, 2><<<grid, block, 0, st>>>(xv, yv, A, B, (int)batch, (int)N, (int)C, r);
     });
 }
 

@@ -1593,17 +1593,17 @@ __global__ __launch_bounds__(kBlock) void cap_bwd_kernel_unaligned(const void* d
 // in flight, and the G partial sums meet in LDS in fixed order -- every row of
 // B is read once per position, not once per lane.  HBM traffic: x once, y once.
 //
-// Backward: G = sum_b dL/dy[b] and dA = G B^T come from one kernel (one block
-// per token, one pass over dL/dy; G goes to a caller-provided N*C fp32
-// workspace), dB = A^T G from a second; the two products are tiny (N*C*r =
-// 4.5 MFLOP at ViT-B/16) next to the pass over dL/dy.
+// Backward: G = sum_b dL/dy[b] comes from one pass over dL/dy (G goes to an N*C
+// fp32 workspace), dA = G B^T and dB = A^T G from a second kernel that reads G
+// out of the caches; the two products are tiny (2 N C r = 9 MFLOP each at
+// ViT-B/16) next to the pass over dL/dy.
 constexpr int kLrpPos = 128;
 constexpr int kLrpGroups = 8;
 constexpr int kLrpFwdBlock = kLrpPos * kLrpGroups;
-constexpr int kLrpTokenBlock = 1024;
-constexpr int kLrpMaxRank = 64;
+constexpr int kLrpMaxRank = 128;  // the paper's scaling study goes to rank 100 (Sec. 4.3, Fig. 5)
+static_assert(kLrpMaxRank <= 2 * 8 * kLrpGroups, "the forward kernel sums the prompt in at most two rounds of 64 ranks");
 
-template <bool BF16>
+template <bool BF16, int ROUNDS>
 __global__ __launch_bounds__(kLrpFwdBlock) void lrp_fwd_kernel(const u32x4* x, u32x4* y,
                                                                const float* __restrict__ A,
                                                                const float* __restrict__ B,
@@ -1630,28 +1630,34 @@ __global__ __launch_bounds__(kLrpFwdBlock) void lrp_fwd_kernel(const u32x4* x, u
         const float* Ai = A + (int64_t)i * r;
         const float* Bc = B + c0;
         const bool b_vectors = ((uintptr_t)B & 15u) == 0;  // C and c0 are multiples of EPV, so rows follow B
-        constexpr int KU = kLrpMaxRank / kLrpGroups;       // all of this group's rows of B in flight
-        float a[KU];
-        u32x4 bk[KU][EPV / 4];
+        constexpr int KU = 8;  // rows of B this group has in flight at a time: 64 ranks per round over the groups
+        // ROUNDS is fixed at compile time (1 for the paper's ranks up to 64): a run-time loop made
+        // the first loads of x wait at its back edge (forward 9.3 -> 13.6 us at ViT-B/16)
 #pragma unroll
-        for (int q = 0; q < KU; ++q) {
-            const int k = grp + q * kLrpGroups;
-            if (k < r) {
-                a[q] = Ai[k];
+        for (int round = 0; round < ROUNDS; ++round) {
+            const int k0 = round * KU * kLrpGroups;
+            float a[KU];
+            u32x4 bk[KU][EPV / 4];
 #pragma unroll
-                for (int h = 0; h < EPV / 4; ++h) {
-                    const float* src = Bc + (int64_t)k * C + 4 * h;
-                    if (b_vectors) bk[q][h] = *(const u32x4*)src;
-                    else bk[q][h] = u32x4{as_u32(src[0]), as_u32(src[1]), as_u32(src[2]), as_u32(src[3])};
+            for (int q = 0; q < KU; ++q) {
+                const int k = k0 + grp + q * kLrpGroups;
+                if (k < r) {
+                    a[q] = Ai[k];
+#pragma unroll
+                    for (int h = 0; h < EPV / 4; ++h) {
+                        const float* src = Bc + (int64_t)k * C + 4 * h;
+                        if (b_vectors) bk[q][h] = *(const u32x4*)src;
+                        else bk[q][h] = u32x4{as_u32(src[0]), as_u32(src[1]), as_u32(src[2]), as_u32(src[3])};
+                    }
                 }
             }
+#pragma unroll
+            for (int q = 0; q < KU; ++q)
+                if (k0 + grp + q * kLrpGroups < r) {
+#pragma unroll
+                    for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a[q], as_f32(bk[q][j / 4][j % 4]), p[j]);
+                }
         }
-#pragma unroll
-        for (int q = 0; q < KU; ++q)
-            if (grp + q * kLrpGroups < r) {
-#pragma unroll
-                for (int j = 0; j < EPV; ++j) p[j] = __builtin_fmaf(a[q], as_f32(bk[q][j / 4][j % 4]), p[j]);
-            }
     }
 #pragma unroll
     for (int j = 0; j < EPV; ++j) part[grp][pos * EPV + j] = p[j];
@@ -1684,138 +1690,185 @@ __global__ __launch_bounds__(kLrpFwdBlock) void lrp_fwd_kernel(const u32x4* x, u
     }
 }
 
-// Backward, first kernel: one block of kLrpTokenBlock lanes per token i.
-//   G[i, c]  = sum_b dy[b, i, c]            (fp32, written to the workspace)
-//   dA[i, k] = sum_c G[i, c] B[k, c]
-// A sample holds only ~150 k elements, so the batch is what fills the chip: the
-// token's channel vectors are spread over the lanes S times, copy s summing the
-// samples s, s+S, s+2S, ... with eight 16-byte loads in flight, and the S
-// partial rows meet in LDS (fixed order, so the result does not depend on the
-// launch).  The row of G then stays in LDS for the products with B: lane
-// (k, q) of 32 x 32 takes channels q, q+32, ... of prompt row k, and the 32
-// partial sums of a k are added by cross-lane moves.  Rows wider than
-// kLrpTokenBlock vectors are taken in chunks.
+// Backward, first kernel: G = sum_b dL/dy[b] in fp32, one pass over dL/dy.  A block is
+// kLrpSumPos neighbouring 16-byte vector positions of the sample times kLrpSumSlices batch
+// slices: slice s of a position adds the samples s, s + S, s + 2S, ... with eight loads in
+// flight, and the S partial sums meet in LDS in fixed order (the result does not depend on the
+// launch).  Positions, not token rows, are what is spread over the blocks: a few hundred
+// 32-position chunks fill the chip evenly whatever N is (one block per token left a quarter of
+// the compute units idle at N = 197 and gave one unit two blocks at N = 257).
+constexpr int kLrpSumPos = 32, kLrpSumSlices = 8, kLrpSumBlock = kLrpSumPos * kLrpSumSlices;
 
 template <bool BF16>
-__global__ __launch_bounds__(kLrpTokenBlock) void lrp_grad_token_kernel(const u32x4* dy,
-                                                                        const float* __restrict__ B,
-                                                                        float* __restrict__ G,
-                                                                        float* __restrict__ dA,
-                                                                        int batch, int N, int C, int r)
+__global__ __launch_bounds__(kLrpSumBlock) void lrp_batch_sum_kernel(const u32x4* dy, float* __restrict__ G,
+                                                                     int batch, int64_t sample)
 {
     constexpr int EPV = BF16 ? 8 : 4;
-    extern __shared__ __align__(16) float lrp_lds[];
-    const int i = blockIdx.x, tid = threadIdx.x;
-    const int vpt = C / EPV;                           // vectors per token row
-    const int64_t sample = (int64_t)N * vpt;           // vectors per sample
-    const int kq = tid & 31, kk = tid >> 5;            // the (k, q) role of the second half
-    float da0 = 0.0f, da1 = 0.0f;                      // prompt rows kk and kk + 32
-
-    for (int v0 = 0; v0 < vpt; v0 += kLrpTokenBlock) {
-        const int cv = vpt - v0 < kLrpTokenBlock ? vpt - v0 : kLrpTokenBlock;  // vectors in this chunk
-        const int S = kLrpTokenBlock / cv;             // copies of the chunk over the lanes
-        const int cc = cv * EPV;                       // channels in this chunk
-        float* part = lrp_lds;                         // [S][cc]
-        float* grow = lrp_lds + S * cc;                // [cc]
-        const int s = tid / cv, v = tid - s * cv;
-        if (s < S) {
-            float acc[EPV];
+    constexpr int U = 8;
+    __shared__ __align__(16) float part[kLrpSumSlices][kLrpSumPos * EPV];
+    const int pos = threadIdx.x % kLrpSumPos, slice = threadIdx.x / kLrpSumPos;
+    const int64_t at = (int64_t)blockIdx.x * kLrpSumPos + pos;  // this lane's vector inside a sample
+    float acc[EPV];
 #pragma unroll
-            for (int j = 0; j < EPV; ++j) acc[j] = 0.0f;
-            const u32x4* src = dy + (int64_t)i * vpt + v0 + v;
-            constexpr int U = 8;
-            for (int b0 = s; b0 < batch; b0 += S * U) {
-                u32x4 t[U];
+    for (int j = 0; j < EPV; ++j) acc[j] = 0.0f;
+    if (at < sample) {
+        const u32x4* src = dy + at;
+        for (int b0 = slice; b0 < batch; b0 += kLrpSumSlices * U) {
+            u32x4 t[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (b0 + u * S < batch) t[u] = stream_load128(src + (int64_t)(b0 + u * S) * sample);
+            for (int u = 0; u < U; ++u)
+                if (b0 + u * kLrpSumSlices < batch) t[u] = stream_load128(src + (int64_t)(b0 + u * kLrpSumSlices) * sample);
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (b0 + u * S < batch) {
-                        float f[EPV];
-                        unpack_vector<BF16>(t[u], f);
+            for (int u = 0; u < U; ++u)
+                if (b0 + u * kLrpSumSlices < batch) {
+                    float f[EPV];
+                    unpack_vector<BF16>(t[u], f);
 #pragma unroll
-                        for (int j = 0; j < EPV; ++j) acc[j] += f[j];
-                    }
-            }
-#pragma unroll
-            for (int j = 0; j < EPV; ++j) part[s * cc + v * EPV + j] = acc[j];
+                    for (int j = 0; j < EPV; ++j) acc[j] += f[j];
+                }
         }
-        __syncthreads();
-        for (int c = tid; c < cc; c += kLrpTokenBlock) {
-            float g = 0.0f;
-            for (int q = 0; q < S; ++q) g += part[q * cc + c];
-            grow[c] = g;
-            G[(int64_t)i * C + v0 * EPV + c] = g;
-        }
-        __syncthreads();
-        const float* Bc = B + v0 * EPV;
-        auto dot_row = [&](int k, float acc) {  // eight loads of B in flight
-            const float* Bk = Bc + (int64_t)k * C;
-            int c = kq;
-            for (; c + 7 * 32 < cc; c += 8 * 32) {
-                float bk[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) bk[u] = Bk[c + 32 * u];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) acc = __builtin_fmaf(grow[c + 32 * u], bk[u], acc);
-            }
-            for (; c < cc; c += 32) acc = __builtin_fmaf(grow[c], Bk[c], acc);
-            return acc;
-        };
-        if (kk < r) da0 = dot_row(kk, da0);
-        if (kk + 32 < r) da1 = dot_row(kk + 32, da1);
-        __syncthreads();                               // the next chunk overwrites part and grow
     }
-    // add up the 32 lanes of a (k) group: two DPP rows of 16, then across the rows
-    auto sum32 = [](float x) {
-        x += dpp_move<kDppXor1>(x);
-        x += dpp_move<kDppXor2>(x);
-        x += dpp_move<kDppHalfMirror>(x);
-        x += dpp_move<kDppMirror>(x);
-        x += __shfl_xor(x, 16, kWave);
-        return x;
-    };
-    da0 = sum32(da0);
-    da1 = sum32(da1);
-    if (kq == 0) {
-        if (kk < r) dA[(int64_t)i * r + kk] = da0;
-        if (kk + 32 < r) dA[(int64_t)i * r + kk + 32] = da1;
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) part[slice][pos * EPV + j] = acc[j];
+    __syncthreads();
+    // kLrpSumPos * EPV sums per block, one per lane (fp32 storage: the first half of the lanes)
+    const int e = threadIdx.x;
+    const int64_t first = (int64_t)blockIdx.x * kLrpSumPos * EPV;
+    if (e < kLrpSumPos * EPV && first + e < sample * EPV) {
+        float g = part[0][e];
+#pragma unroll
+        for (int q = 1; q < kLrpSumSlices; ++q) g += part[q][e];
+        G[first + e] = g;
     }
 }
 
-// Backward, second kernel: dB[k, c] = sum_i A[i, k] G[i, c].  blockIdx.y = k; a
-// block covers 64 channels, its sixteen waves split the tokens and add up
-// through LDS.
-constexpr int kLrpGradBBlock = 1024;
-__global__ __launch_bounds__(kLrpGradBBlock) void lrp_grad_b_kernel(const float* __restrict__ G,
-                                                                    const float* __restrict__ A,
-                                                                    float* __restrict__ dB, int N, int C,
-                                                                    int r)
+// Backward, second kernel: the two small products, from G (fp32, N x C),
+//   dB[k, c] = sum_i A[i, k] G[i, c]        blocks [0, blocks_b):  32 channels, 8 ranks
+//   dA[i, k] = sum_c G[i, c] B[k, c]        the rest:              one token, 4 ranks
+// (the few dB blocks have the longer chain of dependent steps, so they come first in the grid and
+// start at once; behind the many short dA blocks they started late and the kernel took twice as long)
+// 2 N C r flops each -- 24 MFLOP at ViT-L/16 and rank 30, 100 MFLOP at rank 100: far too little
+// for the matrix cores to matter.  What costs is latency: G was written a moment ago by other
+// compute units, so its first touch here comes from beyond this XCD's L2 (1-2 us), and every
+// further round of dependent loads costs that again (a first version with four rounds of four
+// loads took 8 us at any size).  So the lanes are laid out so that ONE round of 16-byte loads
+// covers a block's share: dA gives each (token, rank) pair a whole wave that strides the channels
+// (C / 256 loads of G and of B per lane, all in flight up to C = 2048; six cross-lane adds; one
+// block per token that walks its ranks four at a time is slower, 8.9 us: its rounds are in series); dB
+// gives each group of 4 channels 32 lanes that stride the tokens (N / 32 loads of G per lane, all
+// requested before the block's slab of A is copied to LDS), and the 32 partial sums meet in LDS in
+// fixed order.  Every element of G is read r / 4 + r / 8 times, from the caches -- into two of
+// the eight L2s: the blocks that share a row (dA) or a slab of columns (dB) are numbered so
+// that they run on the same XCD.
+constexpr int kXcds = 8;  // accelerator dies; block b of a grid runs on die b % 8
+constexpr int kLrpAbBlock = 256, kLrpDaRanks = 4, kLrpRankTile = 8, kLrpDbChannels = 32, kLrpSlab = 512;
+
+__device__ __forceinline__ float4 load_f32x4(const float* p, bool vectors)
 {
-    constexpr int W = kLrpGradBBlock / kWave;
-    __shared__ float part[W][kWave];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int c = blockIdx.x * kWave + lane;
-    const int k = blockIdx.y;
-    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;  // independent chains
-    if (c < C) {
-        int i = wave;
-        for (; i + 3 * W < N; i += 4 * W) {
-            a0 = __builtin_fmaf(A[(int64_t)i * r + k], G[(int64_t)i * C + c], a0);
-            a1 = __builtin_fmaf(A[(int64_t)(i + W) * r + k], G[(int64_t)(i + W) * C + c], a1);
-            a2 = __builtin_fmaf(A[(int64_t)(i + 2 * W) * r + k], G[(int64_t)(i + 2 * W) * C + c], a2);
-            a3 = __builtin_fmaf(A[(int64_t)(i + 3 * W) * r + k], G[(int64_t)(i + 3 * W) * C + c], a3);
-        }
-        for (; i < N; i += W) a0 = __builtin_fmaf(A[(int64_t)i * r + k], G[(int64_t)i * C + c], a0);
-    }
-    part[wave][lane] = (a0 + a1) + (a2 + a3);
-    __syncthreads();
-    if (wave == 0 && c < C) {
-        float v = 0.0f;
+    if (vectors) return *(const float4*)p;
+    return float4{p[0], p[1], p[2], p[3]};
+}
+
+__global__ __launch_bounds__(kLrpAbBlock) void lrp_grad_ab_kernel(const float* __restrict__ G,
+                                                                  const float* __restrict__ A,
+                                                                  const float* __restrict__ B,
+                                                                  float* __restrict__ dA, float* __restrict__ dB,
+                                                                  int N, int C, int r, int blocks_b)
+{
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x >= blocks_b) {
+        // ---- dA: token i, ranks k0 .. k0 + 3; wave kk takes rank k0 + kk, lane q the channel vectors q, q + 64, ...
+        // all rank tiles of a token run on one XCD (consecutive block numbers go round the 8 XCDs), so that
+        // a row of G comes into one L2 only
+        const int tiles = (r + kLrpDaRanks - 1) / kLrpDaRanks;
+        const int ba = blockIdx.x - blocks_b;
+        const int i = (ba / kXcds / tiles) * kXcds + ba % kXcds, k0 = ((ba / kXcds) % tiles) * kLrpDaRanks;
+        if (i >= N) return;  // N rounded up to whole groups of 8 tokens
+        const int kk = tid >> 6, q = tid & 63, k = k0 + kk;
+        const bool vec = (((uintptr_t)G | (uintptr_t)B) & 15u) == 0;  // rows are whole vectors: C % 4 == 0
+        const float* Gi = G + (int64_t)i * C;
+        const float* Bk = B + (int64_t)(k < r ? k : r - 1) * C;      // waves past the rank recompute the last row
+        const int nv = C / 4;
+        float acc = 0.0f;
+        constexpr int U = 8;
+        for (int v0 = q; v0 < nv; v0 += kWave * U) {
+            float4 g[U], b[U];
 #pragma unroll
-        for (int w = 0; w < W; ++w) v += part[w][lane];
-        dB[(int64_t)k * C + c] = v;
+            for (int u = 0; u < U; ++u)
+                if (v0 + kWave * u < nv) {
+                    g[u] = load_f32x4(Gi + 4 * (v0 + kWave * u), vec);
+                    b[u] = load_f32x4(Bk + 4 * (v0 + kWave * u), vec);
+                }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (v0 + kWave * u < nv) {
+                    acc = __builtin_fmaf(g[u].x, b[u].x, acc);
+                    acc = __builtin_fmaf(g[u].y, b[u].y, acc);
+                    acc = __builtin_fmaf(g[u].z, b[u].z, acc);
+                    acc = __builtin_fmaf(g[u].w, b[u].w, acc);
+                }
+        }
+        acc = group_sum<kWave>(acc);
+        if (q == 0 && k < r) dA[(int64_t)i * r + k] = acc;
+        return;
+    }
+    // ---- dB: channels c0 .. c0 + 31, ranks k0 .. k0 + 7; lane (slice, c4): tokens slice, slice + 32, ...
+    constexpr int C4 = kLrpDbChannels / 4, SLICES = kLrpAbBlock / C4;  // 8 channel vectors, 32 token slices
+    constexpr int U = kLrpSlab / SLICES;                               // 16: a slab's tokens of one slice
+    __shared__ __align__(16) float a_slab[kLrpSlab * kLrpRankTile];                   // A[i0 .. i0 + 511, k0 .. k0 + 7]
+    __shared__ __align__(16) float part[SLICES][kLrpRankTile][kLrpDbChannels];        // 32 KB
+    const int tiles = (r + kLrpRankTile - 1) / kLrpRankTile;
+    // likewise all rank tiles of a slab of channels on one XCD
+    const int b = blockIdx.x;
+    const int k0 = ((b / kXcds) % tiles) * kLrpRankTile, c0 = ((b / kXcds / tiles) * kXcds + b % kXcds) * kLrpDbChannels;
+    if (c0 >= C) return;  // slabs rounded up to whole groups of 8 (before any barrier, the whole block)
+    const int c4 = tid % C4, slice = tid / C4;
+    const int c = c0 + 4 * c4;
+    const bool live = c < C;  // C % 4 == 0: a vector is inside or outside as a whole
+    const bool vec = ((uintptr_t)G & 15u) == 0;
+    float acc[kLrpRankTile][4];
+#pragma unroll
+    for (int k = 0; k < kLrpRankTile; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[k][j] = 0.0f;
+    for (int i0 = 0; i0 < N; i0 += kLrpSlab) {  // tokens in slabs (one slab for the paper's models)
+        const int ni = N - i0 < kLrpSlab ? N - i0 : kLrpSlab;
+        float4 g[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (live && slice + SLICES * u < ni) g[u] = load_f32x4(G + (int64_t)(i0 + slice + SLICES * u) * C + c, vec);
+        __syncthreads();  // the slab of the round before has been used up
+        for (int e = tid; e < ni * kLrpRankTile; e += kLrpAbBlock) {
+            const int ii = e / kLrpRankTile, k = e % kLrpRankTile;
+            a_slab[e] = k0 + k < r ? A[(int64_t)(i0 + ii) * r + k0 + k] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (live && slice + SLICES * u < ni) {
+                const float4 a_lo = *(const float4*)&a_slab[(slice + SLICES * u) * kLrpRankTile];
+                const float4 a_hi = *(const float4*)&a_slab[(slice + SLICES * u) * kLrpRankTile + 4];
+                const float a[kLrpRankTile] = {a_lo.x, a_lo.y, a_lo.z, a_lo.w, a_hi.x, a_hi.y, a_hi.z, a_hi.w};
+#pragma unroll
+                for (int k = 0; k < kLrpRankTile; ++k) {
+                    acc[k][0] = __builtin_fmaf(a[k], g[u].x, acc[k][0]);
+                    acc[k][1] = __builtin_fmaf(a[k], g[u].y, acc[k][1]);
+                    acc[k][2] = __builtin_fmaf(a[k], g[u].z, acc[k][2]);
+                    acc[k][3] = __builtin_fmaf(a[k], g[u].w, acc[k][3]);
+                }
+            }
+    }
+#pragma unroll
+    for (int k = 0; k < kLrpRankTile; ++k)
+        *(float4*)&part[slice][k][4 * c4] = float4{acc[k][0], acc[k][1], acc[k][2], acc[k][3]};
+    __syncthreads();
+    // 8 ranks x 32 channels = 256 sums, one per lane, channels fastest
+    {
+        const int k = tid / kLrpDbChannels, cc = tid % kLrpDbChannels;
+        float v = part[0][k][cc];
+#pragma unroll
+        for (int q = 1; q < SLICES; ++q) v += part[q][k][cc];
+        if (k0 + k < r && c0 + cc < C) dB[(int64_t)(k0 + k) * C + c0 + cc] = v;
     }
 }
 

@@ -89,17 +89,36 @@ def test_shapes(dtype, shape):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r", [5, 15, 30, 50, 70, 100, 127, 128])
+def test_ranks_of_the_scaling_study(dtype, r):
+    """Sec. 4.3 ("Scaling Tunable Parameters Up", Fig. 5) runs the prompt at ranks 5 .. 100; 128 is the
+    library's limit.  Ranks above 64 take two rounds of the forward kernel's prompt sum, and every rank
+    that is not a multiple of 8 leaves a ragged last rank tile in the backward products."""
+    _check(4, 37, 256, r, dtype, seed=1000 + r)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_vit_l16_tokens_rank_100(dtype):
+    _check(8, 197, 1024, 100, dtype, seed=4100)
+
+
+def test_more_tokens_than_one_slab():
+    """N above 512: the backward products walk A in slabs of 512 tokens."""
+    _check(2, 1300, 64, 9, wl.BF16, seed=1300)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("vectors", [512, 513, 1024, 1025, 2049])
 def test_wide_rows(dtype, vectors):
-    """Rows of 512 .. 2049 16-byte vectors: one or several copies of the row over the token block's
-    lanes, and rows taken in chunks of 1024 vectors."""
+    """Rows of 512 .. 2049 16-byte vectors: the backward products stride such rows in several rounds
+    of eight loads, and the channel count is not a multiple of 64 or 128."""
     C = vectors * (8 if dtype == wl.BF16 else 4)
     _check(3, 2, C, 7, dtype, seed=vectors)
 
 
 def test_swin_stage_shape():
-    """Many tokens, few channels ([16, 3136, 128], the first Swin-B stage): 64 copies of a token's
-    channel vectors per block in the backward kernel."""
+    """Many tokens, few channels ([16, 3136, 128], the first Swin-B stage): seven slabs of tokens in
+    the backward products."""
     _check(16, 3136, 128, 30, wl.BF16, seed=3136)
 
 
@@ -149,7 +168,7 @@ def test_argument_errors():
     f = 0x1000
     assert s2a.lrp_fwd(f, f, f, f, 2, 3, 10, 4, s2a.BF16, check=False) == s2a.ERR_SIZE     # C not a multiple of 8
     assert s2a.lrp_fwd(f, f, f, f, 2, 3, 16, 0, s2a.BF16, check=False) == s2a.ERR_SIZE
-    assert s2a.lrp_fwd(f, f, f, f, 2, 3, 16, 65, s2a.BF16, check=False) == s2a.ERR_SIZE
+    assert s2a.lrp_fwd(f, f, f, f, 2, 3, 16, 129, s2a.BF16, check=False) == s2a.ERR_SIZE
     assert s2a.lrp_fwd(f, f, f, f, 2, 3, 16, 4, 7, check=False) == s2a.ERR_DTYPE
     assert s2a.lrp_fwd(f, None, f, f, 2, 3, 16, 4, s2a.BF16, check=False) == s2a.ERR_NULL
     assert s2a.lrp_fwd(f + 2, f, f, f, 2, 3, 16, 4, s2a.BF16, check=False) == s2a.ERR_ALIGN
