@@ -410,14 +410,16 @@ int launch_cap_g(bool fwd, const void* in, void* out, int64_t n_out, hipStream_t
     const int64_t n_in = n_out * R;
     const int64_t nvec = n_in / EPV;
     const int64_t slots = nvec + (n_in % EPV != 0);
-    const int64_t blocks = (slots + s2a::kWave - 1) / s2a::kWave;
+    const int bs = s2a::kCapBlock;
+    const int64_t per = fwd ? (int64_t)bs * s2a::kCapFwdVectors : bs;  // vectors per block
+    const int64_t blocks = (slots + per - 1) / per;
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     return checked_launch([&] {
         if (fwd)
-            s2a::cap_fwd_kernel<BF16, R><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(
+            s2a::cap_fwd_kernel<BF16, R, s2a::kCapFwdVectors><<<dim3((unsigned)blocks), dim3(bs), 0, st>>>(
                 (const s2a::u32x4*)in, out, n_in, nvec);
         else
-            s2a::cap_bwd_kernel<BF16, R><<<dim3((unsigned)blocks), dim3(s2a::kWave), 0, st>>>(
+            s2a::cap_bwd_kernel<BF16, R><<<dim3((unsigned)blocks), dim3(bs), 0, st>>>(
                 in, (s2a::u32x4*)out, n_in, nvec);
     });
 }

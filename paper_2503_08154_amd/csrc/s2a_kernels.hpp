@@ -1463,6 +1463,16 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_kernel(const void* 
 // neighbouring lanes add up by DPP moves and the first of them stores.
 // Bytes per input element: e + e/R in either direction.
 
+// Lanes per block and vectors per lane of the pooling kernels, by measurement at [64, 197, 4096]
+// bf16, r = 8 (forward 116 MB, mostly read; backward the same bytes, mostly written): single-wave
+// blocks with one vector per lane, the shape of the activation kernels, reach 59 % / 64 % of the
+// HBM peak here -- such waves are so short-lived that the launch rate of waves (about 4.6 per ns)
+// limits them.  Forward: 128 lanes x 4 vectors 73 % (x 1: 64 %, x 2: 70 %, x 8: 73 %; 256 lanes
+// the same within 1 %; sending a wave's 64 two-byte outputs out through 8 lanes as 16-byte vectors
+// gains 2 % there and loses 8 % at the token shapes, where the kernel is a few microseconds long:
+// not used).  Backward: 128 lanes 88 %, 256 lanes 86 %.
+constexpr int kCapBlock = 128, kCapFwdVectors = 4;
+
 template <bool BF16>
 __device__ __forceinline__ void unpack_vector(const u32x4& v, float* f)
 {
@@ -1478,57 +1488,72 @@ __device__ __forceinline__ void unpack_vector(const u32x4& v, float* f)
     }
 }
 
-template <bool BF16, int R>
-__global__ __launch_bounds__(kWave) void cap_fwd_kernel(const u32x4* x, void* y, int64_t n_in,
-                                                        int64_t nvec)
+// V vectors per lane, all requested before the first is used: a kernel that mostly reads needs more
+// bytes in flight per wave than the read-and-write kernels above (their waves live long enough on
+// their stores).  Lane t of a block takes the vectors t, t + B, t + 2B, ... of the block's chunk.
+template <bool BF16, int R, int V>
+__global__ __launch_bounds__(kCapBlock) void cap_fwd_kernel(const u32x4* x, void* y, int64_t n_in,
+                                                            int64_t nvec)
 {
     constexpr int EPV = BF16 ? 8 : 4;
     constexpr float kInv = 1.0f / (float)R;
-    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
-    if constexpr (R <= EPV) {
-        constexpr int OUT = EPV / R;  // outputs per lane
-        if (i < nvec) {
-            float f[EPV], o[OUT];
-            unpack_vector<BF16>(stream_load128(x + i), f);
+    const int64_t first = (int64_t)blockIdx.x * (blockDim.x * V) + threadIdx.x;
+    u32x4 t[V];
+    if (nvec > 0) {
 #pragma unroll
-            for (int q = 0; q < OUT; ++q) {
-                float acc = f[q * R];
-#pragma unroll
-                for (int j = 1; j < R; ++j) acc += f[q * R + j];
-                o[q] = acc * kInv;
-            }
-#pragma unroll
-            for (int q = 0; q < OUT; ++q) store_elem<BF16>(y, i * OUT + q, o[q]);
-        } else if (i == nvec) {  // leftover groups past the last full vector
-            for (int64_t m = nvec * OUT; m < n_in / R; ++m) {
-                float acc = 0.0f;
-                for (int j = 0; j < R; ++j) acc += load_elem<BF16>(x, m * R + j);
-                store_elem<BF16>(y, m, acc * kInv);
-            }
+        for (int v = 0; v < V; ++v) {
+            const int64_t i = first + (int64_t)v * blockDim.x;
+            t[v] = stream_load128(x + (i < nvec ? i : nvec - 1));  // lanes past the end re-read the last vector
         }
-    } else {
-        constexpr int K = R / EPV;  // lanes per output, 2..16: stays inside a DPP row
-        // every lane takes part in the DPP moves; lanes past the end recompute the last vector
-        float f[EPV];
-        unpack_vector<BF16>(stream_load128(x + (i < nvec ? i : nvec - 1)), f);
-        float acc = f[0];
+    }
 #pragma unroll
-        for (int j = 1; j < EPV; ++j) acc += f[j];
-        acc += dpp_move<kDppXor1>(acc);
-        if (K >= 4) acc += dpp_move<kDppXor2>(acc);
-        if (K >= 8) acc += dpp_move<kDppHalfMirror>(acc);
-        if (K >= 16) acc += dpp_move<kDppMirror>(acc);
-        if (i < nvec && (threadIdx.x % K) == 0) store_elem<BF16>(y, i / K, acc * kInv);
+    for (int v = 0; v < V; ++v) {
+        const int64_t i = first + (int64_t)v * blockDim.x;
+        if constexpr (R <= EPV) {
+            constexpr int OUT = EPV / R;  // outputs per lane
+            if (i < nvec) {
+                float f[EPV], o[OUT];
+                unpack_vector<BF16>(t[v], f);
+#pragma unroll
+                for (int q = 0; q < OUT; ++q) {
+                    float acc = f[q * R];
+#pragma unroll
+                    for (int j = 1; j < R; ++j) acc += f[q * R + j];
+                    o[q] = acc * kInv;
+                }
+#pragma unroll
+                for (int q = 0; q < OUT; ++q) store_elem<BF16>(y, i * OUT + q, o[q]);
+            } else if (i == nvec) {  // leftover groups past the last full vector
+                for (int64_t m = nvec * OUT; m < n_in / R; ++m) {
+                    float acc = 0.0f;
+                    for (int j = 0; j < R; ++j) acc += load_elem<BF16>(x, m * R + j);
+                    store_elem<BF16>(y, m, acc * kInv);
+                }
+            }
+        } else {
+            constexpr int K = R / EPV;  // lanes per output, 2..16: stays inside a DPP row
+            // every lane takes part in the DPP moves (n_in is a multiple of R > EPV, so nvec > 0 here)
+            float f[EPV];
+            unpack_vector<BF16>(t[v], f);
+            float acc = f[0];
+#pragma unroll
+            for (int j = 1; j < EPV; ++j) acc += f[j];
+            acc += dpp_move<kDppXor1>(acc);
+            if (K >= 4) acc += dpp_move<kDppXor2>(acc);
+            if (K >= 8) acc += dpp_move<kDppHalfMirror>(acc);
+            if (K >= 16) acc += dpp_move<kDppMirror>(acc);
+            if (i < nvec && (threadIdx.x % K) == 0) store_elem<BF16>(y, i / K, acc * kInv);
+        }
     }
 }
 
 template <bool BF16, int R>
-__global__ __launch_bounds__(kWave) void cap_bwd_kernel(const void* dy, u32x4* dx, int64_t n_in,
-                                                        int64_t nvec)
+__global__ __launch_bounds__(kCapBlock) void cap_bwd_kernel(const void* dy, u32x4* dx, int64_t n_in,
+                                                            int64_t nvec)
 {
     constexpr int EPV = BF16 ? 8 : 4;
     constexpr float kInv = 1.0f / (float)R;
-    const int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < nvec) {
         float f[EPV];
         if constexpr (R >= EPV) {
