@@ -227,36 +227,55 @@ def time_tiny(torch, steps: int, warmup: int):
     return res
 
 
-def time_copy_ceiling(torch, n: int, dtype: int, shape: str, sets: int, steps: int, warmup: int):
-    """A math-free kernel with the launch shape, the memory instructions and the traffic of an
-    activation kernel (s2a_stream_copy_shaped): shape "fwd" reads 16 bytes per lane and writes 16
-    bytes plus the lane's share of the packed codes; shape "bwd" reads both and writes 16 bytes."""
+def time_copy_ceilings(torch, n: int, dtype: int, sets: int, steps: int, warmup: int):
+    """Math-free kernels with the launch shape, the memory instructions and the traffic of the two
+    activation kernels (s2a_stream_copy_shaped): the forward shape reads 16 bytes per lane and writes
+    16 bytes plus the lane's share of the packed codes, the backward shape reads both and writes 16
+    bytes.  They are timed in the sequence of a step -- a phase of forward-shaped launches over `sets`
+    buffer sets, then a phase of backward-shaped ones in reverse -- because the rate of a phase depends
+    on what ran before it: the first ten or so write-heavy launches after a read-heavy phase run 4 %
+    faster than the same launches in an unbroken series (the chip's power management; an idle gap
+    does not have the effect), and a ceiling measured in an unbroken series sits below the kernel
+    it is meant to bound."""
     nbytes = n * esize(dtype) // 16 * 16
     side = 4 if dtype == wl.BF16 else 2
-    bufs = [(torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(0x3C),
-             torch.empty(nbytes, dtype=torch.uint8, device="cuda"),
-             torch.empty(nbytes // 16 * side, dtype=torch.uint8, device="cuda").fill_(0x5A)) for _ in range(sets)]
-    ptrs = [tuple(t.data_ptr() for t in b) for b in bufs]
+    bufs = [tuple(torch.empty(k, dtype=torch.uint8, device="cuda").fill_(v) for k, v in
+                  ((nbytes, 0x3C), (nbytes, 0), (nbytes // 16 * side, 0x5A), (nbytes, 0x3C), (nbytes, 0)))
+            for _ in range(sets)]
+    P = [tuple(t.data_ptr() for t in b) for b in bufs]  # x, y, codes, dy, dx
     stream = torch.cuda.current_stream().cuda_stream
-    is_in = 1 if shape == "bwd" else 0
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        for p in P:
+            s2a.stream_copy_shaped(p[0], p[1], p[2], nbytes, side, 0, stream)
+        if ev:
+            ev[1].record()
+        for p in reversed(P):
+            s2a.stream_copy_shaped(p[3], p[4], p[2], nbytes, side, 1, stream)
+        if ev:
+            ev[2].record()
+
     for _ in range(warmup):
-        for a, b, c in ptrs:
-            s2a.stream_copy_shaped(a, b, c, nbytes, side, is_in, stream)
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+        step()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     torch.cuda.synchronize()
     for k in range(steps):
-        events[k][0].record()
-        for a, b, c in ptrs:
-            s2a.stream_copy_shaped(a, b, c, nbytes, side, is_in, stream)
-        events[k][1].record()
+        step(events[k])
     torch.cuda.synchronize()
-    us = sum(e[0].elapsed_time(e[1]) for e in events) * 1e3 / (steps * sets)
     moved = 2 * nbytes + nbytes // 16 * side
-    gbs = moved / us / 1e3
+    out = {}
+    for shape, a, b in (("fwd", 0, 1), ("bwd", 1, 2)):
+        us = sum(e[a].elapsed_time(e[b]) for e in events) * 1e3 / (steps * sets)
+        gbs = moved / us / 1e3
+        out[shape] = {"kernel": f"s2a::stream_copy_shaped_kernel<{side}, {'true' if shape == 'bwd' else 'false'}>",
+                      "bytes_per_launch": moved, "us_per_launch": round(us, 2), "gbs": round(gbs, 1),
+                      "frac": round(gbs / HBM_PEAK_GBS, 4), "buffer_sets": sets,
+                      "sequence": "forward-shaped phase then backward-shaped phase, as in a step"}
     del bufs
     torch.cuda.empty_cache()
-    return {"kernel": f"s2a::stream_copy_shaped_kernel<{side}, {'true' if is_in else 'false'}>", "bytes_per_launch": moved,
-            "us_per_launch": round(us, 2), "gbs": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "buffer_sets": sets}
+    return out
 
 
 def kernel_block(res, w: wl.Workload, which: str, traffic, ceiling=None):
@@ -326,7 +345,7 @@ def time_ops(torch, ops, sets: int, steps: int, warmup: int):
 
 
 def row_block(kernel: str, us: float, nbytes: float, traffic, row: str, note: str | None = None):
-    tr = traffic.get((row, kernel.split(" + ")[0]))
+    tr = traffic.get((row, kernel.replace(" ", "")))  # several kernels of one call: their sum, under the joined name
     blk = {"kernel": kernel, "bound": "hbm", "us_per_launch": round(us, 2), "achieved": round(nbytes / us / 1e3, 1),
            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
            "algorithmic_bytes_per_launch": int(nbytes),
@@ -412,7 +431,7 @@ def cap_lrp_row(torch, row: str, batch: int, N: int, C: int, steps: int, warmup:
 
 
 def variant_row(torch, name: str, variant: str, steps: int, warmup: int, traffic, bytes_per_elem_fwd=None,
-                w_override=None, kernels=("fwd", "bwd")):
+                w_override=None, row_key=None):
     """One of the element-wise variants (measured range, SiLU, ReLU mask) on a workload's layers."""
     tw = w_override or wl.WORKLOADS[name]
     if tw.layers == 1:
@@ -428,8 +447,8 @@ def variant_row(torch, name: str, variant: str, steps: int, warmup: int, traffic
           "silu": (f"s2a::fwd_kernel<{dt}, silu>", f"s2a::bwd_kernel<{dt}>"),
           "relu": (f"s2a::relu_fwd_kernel<{dt}>", f"s2a::relu_bwd_kernel<{dt}>")}[variant]
     return {"workload": name, "buffer_sets": tw.layers,
-            "fwd": row_block(kn[0], r["fwd_us_per_launch"], fwd_bytes, traffic, f"{name}:{variant}"),
-            "bwd": row_block(kn[1], r["bwd_us_per_launch"], bwd_bytes, traffic, f"{name}:{variant}")}
+            "fwd": row_block(kn[0], r["fwd_us_per_launch"], fwd_bytes, traffic, row_key or f"{name}:{variant}"),
+            "bwd": row_block(kn[1], r["bwd_us_per_launch"], bwd_bytes, traffic, row_key or f"{name}:{variant}")}
 
 
 def cpu_baseline(w: wl.Workload, target_cpu_seconds: float = 12.0):
@@ -630,7 +649,7 @@ def main():
     subw = max(5, args.warmup)
     n1 = w.sizes()[0]
     ceil_sets = max(8, min(24, res["launches_per_phase"]))
-    ceilings = {k: time_copy_ceiling(torch, n1, w.dtype, k, ceil_sets, sub, 3) for k in ("fwd", "bwd")}
+    ceilings = time_copy_ceilings(torch, n1, w.dtype, ceil_sets, sub, 3)
     out = {
         "metric": METRIC,
         "value": round(value, 1),
@@ -670,7 +689,7 @@ def main():
             r = time_workload(torch, tw, sub, subw, distinct_seeds=False)
             cc = None
             if len(tw.shapes) == 1:
-                cc = {k: time_copy_ceiling(torch, tw.sizes()[0], tw.dtype, k, 8, sub, 3) for k in ("fwd", "bwd")}
+                cc = time_copy_ceilings(torch, tw.sizes()[0], tw.dtype, 8, sub, 3)
             targets[name] = {
                 "workload": f"{name}: {dname(tw.dtype)} " + " + ".join("x".join(map(str, s)) for s in tw.shapes),
                 "buffer_sets": tw.layers,
@@ -691,7 +710,8 @@ def main():
         narrow = wl.Workload(tl.name, tl.index, tl.dtype, tl.shapes, tl.layers, "normal", 0.3, tl.dy_scale)
         rows["measured_range_saturating_input"] = variant_row(torch, "vit_l16", "gelu_dyn", sub, subw, traffic)
         rows["measured_range_narrow_input"] = variant_row(torch, "vit_l16", "gelu_dyn", sub, subw, traffic,
-                                                          bytes_per_elem_fwd=3 * e + 0.5, w_override=narrow)
+                                                          bytes_per_elem_fwd=3 * e + 0.5, w_override=narrow,
+                                                          row_key="vit_l16:gelu_dyn_narrow")
         rows["measured_range_vit_g14_f32"] = variant_row(torch, "vit_g14_f32", "gelu_dyn", sub, subw, traffic)
         rows["silu"] = variant_row(torch, "vit_l16", "silu", sub, subw, traffic)
         rows["relu_mask_vit_l16"] = variant_row(torch, "vit_l16", "relu", sub, subw, traffic)

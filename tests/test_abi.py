@@ -81,6 +81,14 @@ def test_error_paths_need_no_gpu():
     assert s2a.stream_copy(None, fake, 32, check=False) == s2a.ERR_NULL
     assert s2a.stream_copy(fake, odd, 32, check=False) == s2a.ERR_ALIGN
     assert s2a.stream_copy(None, None, 0, check=False) == s2a.OK
+    assert s2a.stream_copy_shaped(fake, fake, fake, 32, 3, 0, check=False) == s2a.ERR_SIZE
+    assert s2a.stream_copy_shaped(fake, fake, fake, 24, 4, 0, check=False) == s2a.ERR_SIZE
+    assert s2a.stream_copy_shaped(fake, fake, None, 32, 4, 1, check=False) == s2a.ERR_NULL
+    assert s2a.stream_copy_shaped(fake, fake, odd, 32, 2, 1, check=False) == s2a.ERR_ALIGN
+    assert s2a.stream_copy_shaped(None, None, None, 0, 4, 0, check=False) == s2a.OK
+    # Low-Rank Prompt: rank and shape limits come before any pointer is looked at
+    assert s2a.lrp_bwd(fake, fake, fake, fake, fake, fake, 2, 3, 16, 129, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.lrp_bwd_noalloc(fake, fake, fake, fake, fake, 2, 3, 16, 0, s2a.F32, check=False) == s2a.ERR_SIZE
 
 
 def test_strerror_is_total():
