@@ -71,8 +71,11 @@ def _check_dx(got_storage, ref, dtype, scale, factor=1.0, skip_rows=None, rows=0
                           f"{got[np.argmax(bad)]!r} vs {ref[np.argmax(bad)]!r}"
 
 
-def _run_and_check(x, dy, dtype, rows, L, offset=0):
+def _run_and_check(x, dy, dtype, rows, L, offset=0, spread=1.0):
+    """`spread` >= 1 widens what depends on hi - lo (the band of the codes, the tolerance of the scale and
+    of the end-to-end dx) for rows whose values are nearly equal: R = hi / (hi - lo) of the flattest row."""
     n = rows * L
+    band_t = BAND_T[dtype] * spread
     es = gu.esize(dtype)
     rb = (L + 1) // 2
     st = torch.cuda.current_stream().cuda_stream
