@@ -476,11 +476,13 @@ int launch_lrp_bwd(const void* dy, const float* A, const float* B, float* dA, fl
     const int epv = dtype == S2A_BF16 ? 8 : 4;
     const int64_t sample = N * (C / epv);  // vectors per sample
     const int64_t sum_blocks = (sample + s2a::kLrpSumPos - 1) / s2a::kLrpSumPos;
-    // tokens (dA) and 32-channel slabs (dB) in whole groups of 8, one member per XCD
+    // token tiles (dA) and 64-channel slabs (dB) in whole groups of 8, one member per XCD
     const int64_t x = s2a::kXcds;
-    const int64_t blocks_a = (N + x - 1) / x * x * ((r + s2a::kLrpDaRanks - 1) / s2a::kLrpDaRanks);
+    const int64_t ktiles = (r + s2a::kLrpTile - 1) / s2a::kLrpTile;
+    const int64_t itiles = (N + s2a::kLrpTile - 1) / s2a::kLrpTile;
     const int64_t slabs = (C + s2a::kLrpDbChannels - 1) / s2a::kLrpDbChannels;
-    const int64_t blocks_b = (slabs + x - 1) / x * x * ((r + s2a::kLrpRankTile - 1) / s2a::kLrpRankTile);
+    const int64_t blocks_a = (itiles + x - 1) / x * x * ktiles;
+    const int64_t blocks_b = (slabs + x - 1) / x * x * ktiles;
     if (sum_blocks > 0x7fffffffLL || blocks_a + blocks_b > 0x7fffffffLL) return S2A_ERR_SIZE;
     int rc = checked_launch([&] {
         if (dtype == S2A_BF16)
@@ -679,8 +681,8 @@ int s2a_lrp_fwd(const void* x, void* y, const float* A, const float* B, int64_t 
     if (!aligned(x, 16) || !aligned(y, 16) || !aligned(A, 4) || !aligned(B, 4)) return S2A_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     const int epv = dtype == S2A_BF16 ? 8 : 4;
-    const int64_t sample = N * (C / epv);               // vectors per sample
-    const int64_t blocks = (sample + s2a::kLrpPos - 1) / s2a::kLrpPos;
+    // a block: kLrpFwdTokens token rows x kLrpFwdCols neighbouring vectors of each
+    const int64_t blocks = ((N + s2a::kLrpFwdTokens - 1) / s2a::kLrpFwdTokens) * ((C / epv + s2a::kLrpFwdCols - 1) / s2a::kLrpFwdCols);
     if (blocks > 0x7fffffffLL) return S2A_ERR_SIZE;
     const dim3 grid((unsigned)blocks), block(s2a::kLrpFwdBlock);
     const s2a::u32x4* xv = (const s2a::u32x4*)x;

@@ -1609,8 +1609,12 @@ __global__ __launch_bounds__(kBlock) void cap_bwd_kernel_unaligned(const void* d
 // over the batch.  Neither x nor y is needed in backward.
 //
 // Forward: the prompt is never materialised in HBM.  A block is kLrpPos
-// neighbouring 16-byte vector positions of the sample (token i, channels
-// c..c+EPV-1) times kLrpGroups lane groups.  Group g of a position streams the
+// 16-byte vector positions of the sample (token i, channels c..c+EPV-1) times
+// kLrpGroups lane groups; the positions are 4 token rows x 32 neighbouring
+// vectors, so that the block's slab of B (r rows of 32 vectors) serves four
+// tokens: with 128 vectors of one row the blocks pulled as many bytes of B out
+// of L2 as of x out of HBM (forward 16.2 -> 12.8 us at [32, 257, 1664], 11.0 ->
+// 10.1 us at [64, 197, 1024]; 8 x 16 is no better, 2 x 64 in between).  Group g of a position streams the
 // samples g, g+G, g+2G, ... from x to y, eight 16-byte loads in flight, so the
 // batch is what fills the chip (a sample holds only ~150 k elements).  The EPV
 // prompt values of a position, P[i, c..] = sum_k A[i,k] B[k,c..], are shared
@@ -1623,6 +1627,8 @@ __global__ __launch_bounds__(kBlock) void cap_bwd_kernel_unaligned(const void* d
 // out of the caches; the two products are tiny (2 N C r = 9 MFLOP each at
 // ViT-B/16) next to the pass over dL/dy.
 constexpr int kLrpPos = 128;
+constexpr int kLrpFwdTokens = 4;                         // a block's positions: this many token rows ...
+constexpr int kLrpFwdCols = kLrpPos / kLrpFwdTokens;     // ... times this many neighbouring vectors of each
 constexpr int kLrpGroups = 8;
 constexpr int kLrpFwdBlock = kLrpPos * kLrpGroups;
 constexpr int kLrpMaxRank = 128;  // the paper's scaling study goes to rank 100 (Sec. 4.3, Fig. 5)
@@ -1640,8 +1646,11 @@ __global__ __launch_bounds__(kLrpFwdBlock) void lrp_fwd_kernel(const u32x4* x, u
     const int pos = threadIdx.x % kLrpPos, grp = threadIdx.x / kLrpPos;
     const int vpt = C / EPV;                            // vectors per token row (the launcher checks C % EPV)
     const int64_t sample = (int64_t)N * vpt;            // vectors per sample
-    const int64_t at = (int64_t)blockIdx.x * kLrpPos + pos;  // this lane's vector inside a sample
-    const bool valid = at < sample;
+    const int col_tiles = (vpt + kLrpFwdCols - 1) / kLrpFwdCols;
+    const int i = (int)(blockIdx.x / col_tiles) * kLrpFwdTokens + pos / kLrpFwdCols;     // token
+    const int q = (int)(blockIdx.x % col_tiles) * kLrpFwdCols + pos % kLrpFwdCols;       // vector inside the token row
+    const bool valid = i < N && q < vpt;
+    const int64_t at = (int64_t)i * vpt + q;  // this lane's vector inside a sample
     // the first round of x is requested before the prompt values are formed: the latencies overlap
     u32x4 v[U];
 #pragma unroll
@@ -1651,7 +1660,7 @@ __global__ __launch_bounds__(kLrpFwdBlock) void lrp_fwd_kernel(const u32x4* x, u
 #pragma unroll
     for (int j = 0; j < EPV; ++j) p[j] = 0.0f;
     if (valid) {
-        const int i = (int)(at / vpt), c0 = (int)(at - (int64_t)i * vpt) * EPV;
+        const int c0 = q * EPV;
         const float* Ai = A + (int64_t)i * r;
         const float* Bc = B + c0;
         const bool b_vectors = ((uintptr_t)B & 15u) == 0;  // C and c0 are multiples of EPV, so rows follow B
@@ -1767,31 +1776,228 @@ __global__ __launch_bounds__(kLrpSumBlock) void lrp_batch_sum_kernel(const u32x4
     }
 }
 
-// Backward, second kernel: the two small products, from G (fp32, N x C),
-//   dB[k, c] = sum_i A[i, k] G[i, c]        blocks [0, blocks_b):  32 channels, 8 ranks
-//   dA[i, k] = sum_c G[i, c] B[k, c]        the rest:              one token, 4 ranks
-// (the few dB blocks have the longer chain of dependent steps, so they come first in the grid and
-// start at once; behind the many short dA blocks they started late and the kernel took twice as long)
-// 2 N C r flops each -- 24 MFLOP at ViT-L/16 and rank 30, 100 MFLOP at rank 100: far too little
-// for the matrix cores to matter.  What costs is latency: G was written a moment ago by other
-// compute units, so its first touch here comes from beyond this XCD's L2 (1-2 us), and every
-// further round of dependent loads costs that again (a first version with four rounds of four
-// loads took 8 us at any size).  So the lanes are laid out so that ONE round of 16-byte loads
-// covers a block's share: dA gives each (token, rank) pair a whole wave that strides the channels
-// (C / 256 loads of G and of B per lane, all in flight up to C = 2048; six cross-lane adds; one
-// block per token that walks its ranks four at a time is slower, 8.9 us: its rounds are in series); dB
-// gives each group of 4 channels 32 lanes that stride the tokens (N / 32 loads of G per lane, all
-// requested before the block's slab of A is copied to LDS), and the 32 partial sums meet in LDS in
-// fixed order.  Every element of G is read r / 4 + r / 8 times, from the caches -- into two of
-// the eight L2s: the blocks that share a row (dA) or a slab of columns (dB) are numbered so
-// that they run on the same XCD.
+// Backward, second kernel: the two small products, from G (fp32, N x C), on the matrix cores:
+//   dB[k, c] = sum_i A[i, k] G[i, c]        blocks [0, blocks_b):  16 ranks x 64 channels, all tokens
+//   dA[i, k] = sum_c G[i, c] B[k, c]        the rest:              16 tokens x 16 ranks, all channels
+// 2 N C r flops each (24 MFLOP at ViT-L/16 and rank 30, 100 MFLOP at rank 100): nothing next to
+// the pass over dL/dy in arithmetic, but as vector code (a wave per (token, rank) dot product, a
+// lane group per column of dB) the two took as long as that pass and twice as long at rank 100:
+// every element of G went from L2 to the compute units r / 4 + r / 8 times.  With
+// v_mfma_f32_16x16x4_f32 (fp32 in, fp32 accumulate) a tile of G serves 16 ranks at once, a
+// block's whole share goes out in one round of 16-byte loads, 8 waves split the contraction index
+// and the 8 partial tiles meet in LDS in fixed order (the result does not depend on the launch).
+// What is left is latency: G was written a moment ago by other compute units, so its first touch
+// here comes from beyond this XCD's L2 (1-2 us), and the launch has only 60-200 blocks.
+//
+// Operand layout of the instruction, lane l = 16 g + m (g = 0..3, m = 0..15):
+//   a: element (row m, contraction index g)        b: element (contraction index g, column m)
+//   d[v], v = 0..3: element (row 4 g + v, column m)
+// The contraction index may be any bijection of the real one as long as a and b use the same,
+// which is what lets a lane feed the four components of one 16-byte vector to four instructions.
+//   dB: rows = ranks, contraction = tokens, columns = channels.  A lane loads G[token][c0 + 4 m .. + 3]
+//       and instruction t takes component t: column m of accumulator t is channel c0 + 4 m + t, so
+//       a wave covers 64 channels and reads 256 contiguous bytes of each of its tokens' rows.
+//   dA: rows = tokens, contraction = channels, columns = ranks: instruction (s, t) contracts the
+//       channels cb + 16 g + 4 s + t, g = 0..3, of the rows G[i0 + m] and B[k0 + m].
+// Rows, columns and contraction indices past the end are fed zeros (both operands where it is the
+// contraction index, so that nothing non-finite meets a zero there).  Blocks that share rows of G
+// (dA) or a slab of its columns (dB) are numbered so that they run on the same XCD.
 constexpr int kXcds = 8;  // accelerator dies; block b of a grid runs on die b % 8
-constexpr int kLrpAbBlock = 256, kLrpDaRanks = 4, kLrpRankTile = 8, kLrpDbChannels = 32, kLrpSlab = 512;
+constexpr int kLrpAbWaves = 8, kLrpAbBlock = kLrpAbWaves * kWave;
+constexpr int kLrpTile = 16;                 // rows and columns of one matrix-core tile
+constexpr int kLrpDbChannels = 4 * kLrpTile; // a dB block's channels: four tiles, interleaved
+constexpr int kLrpDaChunk = 64;              // channels a wave contracts per round of four vectors
 
-__device__ __forceinline__ float4 load_f32x4(const float* p, bool vectors)
+// Straight-line code matters here: around a load that sits under a run-time condition the
+// compiler waits for every outstanding load at the join, which puts the rounds of loads in
+// series.  So nothing is loaded conditionally: an address past the end is replaced by one inside
+// and the value by zero, the alignment case and the number of rounds are template parameters, and
+// the kernel picks the instantiation once, at its top.
+template <bool VEC>
+__device__ __forceinline__ float4 load_f32x4(const float* p, bool live)
 {
-    if (vectors) return *(const float4*)p;
-    return float4{p[0], p[1], p[2], p[3]};
+    float4 v;
+    if constexpr (VEC) v = *(const float4*)p;
+    else v = float4{p[0], p[1], p[2], p[3]};
+    return float4{live ? v.x : 0.0f, live ? v.y : 0.0f, live ? v.z : 0.0f, live ? v.w : 0.0f};
+}
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma_16x16x4(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+constexpr int kLrpDbQuads = 8;   // token quads in flight per wave: 256 tokens per round of a dB block
+constexpr int kLrpDaChunks = 2;  // 64-channel chunks in flight per wave: 1024 channels per round of a dA block
+// (9 quads and 4 chunks, which put N = 257 and C = 1664 into one round, gain 4 % there and cost
+// 10 % at N = 197, C = 1024: the slots past the end still issue their loads)
+
+// ---- dB: ranks k0 .. k0 + 15, channels c0 .. c0 + 63; wave w takes the token quads w, w + 8, ...
+// ROUNDS > 0: that many rounds of 256 tokens, unrolled; 0: as many as N needs.
+template <int ROUNDS, bool VEC>
+__device__ __forceinline__ void lrp_db_tile(const float* __restrict__ G, const float* __restrict__ A,
+                                            float* __restrict__ dB, float (*part)[4][kWave][4], int N, int C, int r,
+                                            int k0, int c0)
+{
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // the same in every lane: conditions on it are scalar
+    const int m = lane % kLrpTile, g = lane / kLrpTile;
+    const bool col_live = c0 + 4 * m < C, row_live = k0 + m < r;  // C % 4 == 0: a vector is inside or outside as a whole
+    const float* Gc = G + (col_live ? c0 + 4 * m : c0);
+    const float* Ak = A + (row_live ? k0 + m : 0);
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 acc[4] = {zero, zero, zero, zero};
+    const int quads = (N + 3) / 4;
+    constexpr int STEP = kLrpAbWaves * kLrpDbQuads;
+    auto one_round = [&](int round) {
+        float4 gv[kLrpDbQuads];
+        float av[kLrpDbQuads];
+#pragma unroll
+        for (int u = 0; u < kLrpDbQuads; ++u) {
+            const int64_t i = 4 * ((int64_t)round * STEP + wave + kLrpAbWaves * u) + g;
+            const bool in = i < N;
+            const int64_t ii = in ? i : 0;
+            gv[u] = load_f32x4<VEC>(Gc + ii * C, in && col_live);
+            const float a = Ak[ii * r];
+            av[u] = in && row_live ? a : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kLrpDbQuads; ++u) {
+            if ((int64_t)round * STEP + wave + kLrpAbWaves * u >= quads) continue;  // the whole wave: nothing but zeros
+            acc[0] = mfma_16x16x4(av[u], gv[u].x, acc[0]);
+            acc[1] = mfma_16x16x4(av[u], gv[u].y, acc[1]);
+            acc[2] = mfma_16x16x4(av[u], gv[u].z, acc[2]);
+            acc[3] = mfma_16x16x4(av[u], gv[u].w, acc[3]);
+        }
+    };
+    if constexpr (ROUNDS > 0) {
+#pragma unroll
+        for (int round = 0; round < ROUNDS; ++round) one_round(round);
+    } else {
+        for (int round = 0; (int64_t)round * STEP < quads; ++round) one_round(round);
+    }
+    // accumulator t, register v of lane (g, m): rank k0 + 4 g + v, channel c0 + 4 m + t
+#pragma unroll
+    for (int v = 0; v < 4; ++v) *(float4*)part[wave][v][lane] = float4{acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+    __syncthreads();
+    if (tid < 4 * kWave) {
+        const int v = tid / kWave, l = tid % kWave, k = k0 + 4 * (l / kLrpTile) + v, cc = c0 + 4 * (l % kLrpTile);
+        float4 sum = *(const float4*)part[0][v][l];
+#pragma unroll
+        for (int w = 1; w < kLrpAbWaves; ++w) {
+            const float4 p = *(const float4*)part[w][v][l];
+            sum.x += p.x, sum.y += p.y, sum.z += p.z, sum.w += p.w;
+        }
+        if (k < r && cc < C) {
+            float* out = dB + (int64_t)k * C + cc;
+            if (((uintptr_t)dB & 15u) == 0) *(float4*)out = sum;
+            else out[0] = sum.x, out[1] = sum.y, out[2] = sum.z, out[3] = sum.w;
+        }
+    }
+}
+
+// ---- dA: tokens i0 .. i0 + 15, ranks k0 .. k0 + 15; wave w takes the 64-channel chunks w, w + 8, ...
+// ROUNDS > 0: that many rounds of 1024 channels, unrolled; 0: as many as C needs.
+// Both operands have the contraction index (channels) along their rows, and the instruction wants
+// neighbouring lanes on neighbouring ROWS: fetched that way a wave-wide load is 64 separate 16-byte
+// pieces, and the address unit, which takes them one line at a time, becomes what the kernel waits
+// for (measured: the kernel's time followed the number of such loads, real or masked).  So a wave
+// fetches its 16 x 64 tile the way memory likes it -- 16 lanes along 256 contiguous bytes of a
+// row, four rows per load -- and turns it through a strip of LDS of its own (rows padded by 16
+// bytes: both the row-wise stores and the operand-wise loads are conflict-free).  LDS
+// instructions of one wave complete in order, so the strip needs no barrier, only a compiler
+// fence between a store and the load of another lane's data.
+constexpr int kLrpStageStride = kLrpDaChunk + 4;                   // floats per staged row
+constexpr int kLrpStageFloats = kLrpTile * kLrpStageStride;        // per wave
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int ROUNDS, bool VEC>
+__device__ __forceinline__ void lrp_da_tile(const float* __restrict__ G, const float* __restrict__ B,
+                                            float* __restrict__ dA, float* lds, int N, int C, int r, int i0, int k0)
+{
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // the same in every lane: conditions on it are scalar
+    const int m = lane % kLrpTile, g = lane / kLrpTile;
+    float* stage = lds + wave * kLrpStageFloats;
+    // fetch: lane (g, m) takes rows g, g + 4, g + 8, g + 12 of the tile, channels 4 m .. 4 m + 3 of the chunk
+    const float* Grow[4];
+    const float* Brow[4];
+    bool tok_live[4], rank_live[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        tok_live[j] = i0 + 4 * j + g < N;
+        rank_live[j] = k0 + 4 * j + g < r;
+        Grow[j] = G + (int64_t)(tok_live[j] ? i0 + 4 * j + g : 0) * C;
+        Brow[j] = B + (int64_t)(rank_live[j] ? k0 + 4 * j + g : 0) * C;
+    }
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    constexpr int STEP = kLrpAbWaves * kLrpDaChunks * kLrpDaChunk;
+    auto one_round = [&](int round) {
+        float4 gv[kLrpDaChunks][4], bv[kLrpDaChunks][4];
+#pragma unroll
+        for (int u = 0; u < kLrpDaChunks; ++u) {
+            const int64_t ch = (int64_t)round * STEP + (wave + kLrpAbWaves * u) * kLrpDaChunk + 4 * m;
+            const bool in = ch < C;
+            const int64_t at = in ? ch : 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                gv[u][j] = load_f32x4<VEC>(Grow[j] + at, in && tok_live[j]);
+                bv[u][j] = load_f32x4<VEC>(Brow[j] + at, in && rank_live[j]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kLrpDaChunks; ++u) {
+            if ((int64_t)round * STEP + (wave + kLrpAbWaves * u) * kLrpDaChunk >= C) continue;  // the whole wave: nothing but zeros
+            float4 ga[4], ba[4];
+            // operand: lane (g, m) takes row m, channels 16 g + 4 s .. + 3 of the chunk for instruction group s
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *(float4*)&stage[(4 * j + g) * kLrpStageStride + 4 * m] = gv[u][j];
+            wave_lds_fence();
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) ga[s4] = *(const float4*)&stage[m * kLrpStageStride + 16 * g + 4 * s4];
+            wave_lds_fence();
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *(float4*)&stage[(4 * j + g) * kLrpStageStride + 4 * m] = bv[u][j];
+            wave_lds_fence();
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) ba[s4] = *(const float4*)&stage[m * kLrpStageStride + 16 * g + 4 * s4];
+            wave_lds_fence();
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                acc = mfma_16x16x4(ga[s4].x, ba[s4].x, acc);
+                acc = mfma_16x16x4(ga[s4].y, ba[s4].y, acc);
+                acc = mfma_16x16x4(ga[s4].z, ba[s4].z, acc);
+                acc = mfma_16x16x4(ga[s4].w, ba[s4].w, acc);
+            }
+        }
+    };
+    if constexpr (ROUNDS > 0) {
+#pragma unroll
+        for (int round = 0; round < ROUNDS; ++round) one_round(round);
+    } else {
+        for (int round = 0; (int64_t)round * STEP < C; ++round) one_round(round);
+    }
+    // register v of lane (g, m): token i0 + 4 g + v, rank k0 + m
+    __syncthreads();  // every wave is done with its strip: the partial tiles go over the same memory
+    float(*part)[kWave][4] = (float(*)[kWave][4])lds;
+    *(float4*)part[wave][lane] = float4{acc[0], acc[1], acc[2], acc[3]};
+    __syncthreads();
+    if (tid < 4 * kWave) {
+        const int v = tid % 4, l = tid / 4;  // the four registers of a lane side by side, as they lie in LDS
+        float sum = part[0][l][v];
+#pragma unroll
+        for (int w = 1; w < kLrpAbWaves; ++w) sum += part[w][l][v];
+        const int i = i0 + 4 * (l / kLrpTile) + v, k = k0 + l % kLrpTile;
+        if (i < N && k < r) dA[(int64_t)i * r + k] = sum;
+    }
 }
 
 __global__ __launch_bounds__(kLrpAbBlock) void lrp_grad_ab_kernel(const float* __restrict__ G,
@@ -1800,101 +2006,32 @@ __global__ __launch_bounds__(kLrpAbBlock) void lrp_grad_ab_kernel(const float* _
                                                                   float* __restrict__ dA, float* __restrict__ dB,
                                                                   int N, int C, int r, int blocks_b)
 {
-    const int tid = threadIdx.x;
-    if ((int)blockIdx.x >= blocks_b) {
-        // ---- dA: token i, ranks k0 .. k0 + 3; wave kk takes rank k0 + kk, lane q the channel vectors q, q + 64, ...
-        // all rank tiles of a token run on one XCD (consecutive block numbers go round the 8 XCDs), so that
-        // a row of G comes into one L2 only
-        const int tiles = (r + kLrpDaRanks - 1) / kLrpDaRanks;
-        const int ba = blockIdx.x - blocks_b;
-        const int i = (ba / kXcds / tiles) * kXcds + ba % kXcds, k0 = ((ba / kXcds) % tiles) * kLrpDaRanks;
-        if (i >= N) return;  // N rounded up to whole groups of 8 tokens
-        const int kk = tid >> 6, q = tid & 63, k = k0 + kk;
-        const bool vec = (((uintptr_t)G | (uintptr_t)B) & 15u) == 0;  // rows are whole vectors: C % 4 == 0
-        const float* Gi = G + (int64_t)i * C;
-        const float* Bk = B + (int64_t)(k < r ? k : r - 1) * C;      // waves past the rank recompute the last row
-        const int nv = C / 4;
-        float acc = 0.0f;
-        constexpr int U = 8;
-        for (int v0 = q; v0 < nv; v0 += kWave * U) {
-            float4 g[U], b[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (v0 + kWave * u < nv) {
-                    g[u] = load_f32x4(Gi + 4 * (v0 + kWave * u), vec);
-                    b[u] = load_f32x4(Bk + 4 * (v0 + kWave * u), vec);
-                }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (v0 + kWave * u < nv) {
-                    acc = __builtin_fmaf(g[u].x, b[u].x, acc);
-                    acc = __builtin_fmaf(g[u].y, b[u].y, acc);
-                    acc = __builtin_fmaf(g[u].z, b[u].z, acc);
-                    acc = __builtin_fmaf(g[u].w, b[u].w, acc);
-                }
-        }
-        acc = group_sum<kWave>(acc);
-        if (q == 0 && k < r) dA[(int64_t)i * r + k] = acc;
+    constexpr int PART = kLrpAbWaves * 4 * kWave * 4, STAGE = kLrpAbWaves * kLrpStageFloats;
+    __shared__ __align__(16) float lds[PART > STAGE ? PART : STAGE];  // 34 KB: dB's partial tiles, or dA's strips
+    const int ktiles = (r + kLrpTile - 1) / kLrpTile;
+    const bool vec = (((uintptr_t)G | (uintptr_t)B) & 15u) == 0;  // rows are whole vectors: C % 4 == 0
+    if ((int)blockIdx.x < blocks_b) {
+        const int b = blockIdx.x;
+        const int k0 = ((b / kXcds) % ktiles) * kLrpTile;
+        const int c0 = ((b / kXcds / ktiles) * kXcds + b % kXcds) * kLrpDbChannels;
+        if (c0 >= C) return;  // slabs rounded up to whole groups of 8 (the whole block, before any barrier)
+        constexpr int TOKENS = 4 * kLrpAbWaves * kLrpDbQuads;  // per round
+        if (!vec) lrp_db_tile<0, false>(G, A, dB, (float(*)[4][kWave][4])lds, N, C, r, k0, c0);
+        else if (N <= TOKENS) lrp_db_tile<1, true>(G, A, dB, (float(*)[4][kWave][4])lds, N, C, r, k0, c0);
+        else if (N <= 2 * TOKENS) lrp_db_tile<2, true>(G, A, dB, (float(*)[4][kWave][4])lds, N, C, r, k0, c0);
+        else lrp_db_tile<0, true>(G, A, dB, (float(*)[4][kWave][4])lds, N, C, r, k0, c0);
         return;
     }
-    // ---- dB: channels c0 .. c0 + 31, ranks k0 .. k0 + 7; lane (slice, c4): tokens slice, slice + 32, ...
-    constexpr int C4 = kLrpDbChannels / 4, SLICES = kLrpAbBlock / C4;  // 8 channel vectors, 32 token slices
-    constexpr int U = kLrpSlab / SLICES;                               // 16: a slab's tokens of one slice
-    __shared__ __align__(16) float a_slab[kLrpSlab * kLrpRankTile];                   // A[i0 .. i0 + 511, k0 .. k0 + 7]
-    __shared__ __align__(16) float part[SLICES][kLrpRankTile][kLrpDbChannels];        // 32 KB
-    const int tiles = (r + kLrpRankTile - 1) / kLrpRankTile;
-    // likewise all rank tiles of a slab of channels on one XCD
-    const int b = blockIdx.x;
-    const int k0 = ((b / kXcds) % tiles) * kLrpRankTile, c0 = ((b / kXcds / tiles) * kXcds + b % kXcds) * kLrpDbChannels;
-    if (c0 >= C) return;  // slabs rounded up to whole groups of 8 (before any barrier, the whole block)
-    const int c4 = tid % C4, slice = tid / C4;
-    const int c = c0 + 4 * c4;
-    const bool live = c < C;  // C % 4 == 0: a vector is inside or outside as a whole
-    const bool vec = ((uintptr_t)G & 15u) == 0;
-    float acc[kLrpRankTile][4];
-#pragma unroll
-    for (int k = 0; k < kLrpRankTile; ++k)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[k][j] = 0.0f;
-    for (int i0 = 0; i0 < N; i0 += kLrpSlab) {  // tokens in slabs (one slab for the paper's models)
-        const int ni = N - i0 < kLrpSlab ? N - i0 : kLrpSlab;
-        float4 g[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (live && slice + SLICES * u < ni) g[u] = load_f32x4(G + (int64_t)(i0 + slice + SLICES * u) * C + c, vec);
-        __syncthreads();  // the slab of the round before has been used up
-        for (int e = tid; e < ni * kLrpRankTile; e += kLrpAbBlock) {
-            const int ii = e / kLrpRankTile, k = e % kLrpRankTile;
-            a_slab[e] = k0 + k < r ? A[(int64_t)(i0 + ii) * r + k0 + k] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (live && slice + SLICES * u < ni) {
-                const float4 a_lo = *(const float4*)&a_slab[(slice + SLICES * u) * kLrpRankTile];
-                const float4 a_hi = *(const float4*)&a_slab[(slice + SLICES * u) * kLrpRankTile + 4];
-                const float a[kLrpRankTile] = {a_lo.x, a_lo.y, a_lo.z, a_lo.w, a_hi.x, a_hi.y, a_hi.z, a_hi.w};
-#pragma unroll
-                for (int k = 0; k < kLrpRankTile; ++k) {
-                    acc[k][0] = __builtin_fmaf(a[k], g[u].x, acc[k][0]);
-                    acc[k][1] = __builtin_fmaf(a[k], g[u].y, acc[k][1]);
-                    acc[k][2] = __builtin_fmaf(a[k], g[u].z, acc[k][2]);
-                    acc[k][3] = __builtin_fmaf(a[k], g[u].w, acc[k][3]);
-                }
-            }
-    }
-#pragma unroll
-    for (int k = 0; k < kLrpRankTile; ++k)
-        *(float4*)&part[slice][k][4 * c4] = float4{acc[k][0], acc[k][1], acc[k][2], acc[k][3]};
-    __syncthreads();
-    // 8 ranks x 32 channels = 256 sums, one per lane, channels fastest
-    {
-        const int k = tid / kLrpDbChannels, cc = tid % kLrpDbChannels;
-        float v = part[0][k][cc];
-#pragma unroll
-        for (int q = 1; q < SLICES; ++q) v += part[q][k][cc];
-        if (k0 + k < r && c0 + cc < C) dB[(int64_t)(k0 + k) * C + c0 + cc] = v;
-    }
+    const int ba = blockIdx.x - blocks_b;
+    const int k0 = ((ba / kXcds) % ktiles) * kLrpTile;
+    const int i0 = ((ba / kXcds / ktiles) * kXcds + ba % kXcds) * kLrpTile;
+    if (i0 >= N) return;  // token tiles rounded up to whole groups of 8
+    constexpr int CHANNELS = kLrpAbWaves * kLrpDaChunks * kLrpDaChunk;  // per round
+    if (!vec) lrp_da_tile<0, false>(G, B, dA, lds, N, C, r, i0, k0);
+    else if (C <= CHANNELS) lrp_da_tile<1, true>(G, B, dA, lds, N, C, r, i0, k0);
+    else if (C <= 2 * CHANNELS) lrp_da_tile<2, true>(G, B, dA, lds, N, C, r, i0, k0);
+    else if (C <= 4 * CHANNELS) lrp_da_tile<4, true>(G, B, dA, lds, N, C, r, i0, k0);
+    else lrp_da_tile<0, true>(G, B, dA, lds, N, C, r, i0, k0);
 }
 
 // ------------------------------------------------- measurement aid --------

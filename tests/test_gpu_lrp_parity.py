@@ -25,7 +25,7 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _check(batch, N, C, r, dtype, seed, inplace=False, b_offset=0):
+def _check(batch, N, C, r, dtype, seed, inplace=False, b_offset=0, out_offset=0):
     g = np.random.Generator(np.random.Philox(seed))
     A = (g.standard_normal((N, r)) * 0.5).astype(np.float32)
     B = (g.standard_normal((r, C)) * 0.5).astype(np.float32)
@@ -65,8 +65,8 @@ def _check(batch, N, C, r, dtype, seed, inplace=False, b_offset=0):
 
     bdy = gu.Buf(n * es).upload(dy)
     bA = gu.Buf(4 * N * r, fill=0xFF)
-    bB = gu.Buf(4 * r * C, fill=0xFF)
-    bw = gu.Buf(4 * N * C, fill=0xFF)
+    bB = gu.Buf(4 * r * C, 4 * out_offset, fill=0xFF)      # out_offset floats off 16-byte alignment
+    bw = gu.Buf(4 * N * C, 4 * out_offset, fill=0xFF)
     s2a.lrp_bwd(bdy.ptr, tA.data_ptr(), tB.data_ptr(), bA.ptr, bB.ptr, bw.ptr, batch, N, C, r, dtype, st)
     torch.cuda.synchronize()
     assert bA.canaries_intact() and bB.canaries_intact() and bw.canaries_intact() and bdy.canaries_intact()
@@ -93,7 +93,7 @@ def test_shapes(dtype, shape):
 def test_ranks_of_the_scaling_study(dtype, r):
     """Sec. 4.3 ("Scaling Tunable Parameters Up", Fig. 5) runs the prompt at ranks 5 .. 100; 128 is the
     library's limit.  Ranks above 64 take two rounds of the forward kernel's prompt sum, and every rank
-    that is not a multiple of 8 leaves a ragged last rank tile in the backward products."""
+    that is not a multiple of 16 leaves a ragged last rank tile in the backward products."""
     _check(4, 37, 256, r, dtype, seed=1000 + r)
 
 
@@ -102,23 +102,24 @@ def test_vit_l16_tokens_rank_100(dtype):
     _check(8, 197, 1024, 100, dtype, seed=4100)
 
 
-def test_more_tokens_than_one_slab():
-    """N above 512: the backward products walk A in slabs of 512 tokens."""
+def test_more_tokens_than_two_rounds():
+    """N above 512: dB takes its tokens in a run-time number of rounds of 256 (one and two rounds are
+    unrolled instantiations)."""
     _check(2, 1300, 64, 9, wl.BF16, seed=1300)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("vectors", [512, 513, 1024, 1025, 2049])
 def test_wide_rows(dtype, vectors):
-    """Rows of 512 .. 2049 16-byte vectors: the backward products stride such rows in several rounds
-    of eight loads, and the channel count is not a multiple of 64 or 128."""
+    """Rows of 512 .. 2049 16-byte vectors: dA contracts such rows in 2, 4 (unrolled) and a run-time
+    number of rounds of 1024 channels, and the channel count is not a multiple of 64."""
     C = vectors * (8 if dtype == wl.BF16 else 4)
     _check(3, 2, C, 7, dtype, seed=vectors)
 
 
 def test_swin_stage_shape():
-    """Many tokens, few channels ([16, 3136, 128], the first Swin-B stage): seven slabs of tokens in
-    the backward products."""
+    """Many tokens, few channels ([16, 3136, 128], the first Swin-B stage): 13 rounds of tokens in dB,
+    196 token tiles in dA."""
     _check(16, 3136, 128, 30, wl.BF16, seed=3136)
 
 
@@ -126,6 +127,19 @@ def test_swin_stage_shape():
 def test_b_not_vector_aligned(dtype):
     """B only 4-byte aligned: the forward kernel's element loads of B."""
     _check(4, 21, 96, 30, dtype, seed=77, b_offset=1)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("off", [1, 2, 3])
+def test_outputs_and_workspace_not_vector_aligned(dtype, off):
+    """dB and the workspace only 4-byte aligned: element stores of dB, element loads of G in both products."""
+    _check(3, 37, 200, 21, dtype, seed=500 + off, out_offset=off)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_vit_g14_tokens(dtype):
+    """[.., 257, 1664]: two rounds of tokens in dB, two rounds of channels in dA, ragged tiles everywhere."""
+    _check(2, 257, 1664, 30, dtype, seed=257)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
