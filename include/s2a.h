@@ -182,12 +182,15 @@ int s2a_relu_bwd(const void* dy, const uint8_t* mask, void* dx, int64_t n, int d
  *                 nibble 0
  *   qparams       device, 2*rows floats, 4-byte aligned: (lo, s) of row r at
  *                 [2r], [2r+1].  A row of equal y has s = 0 and codes 0.
- *   L             1 <= L <= 1024 (else S2A_ERR_SIZE); rows >= 0
+ *   L             1 <= L <= S2A_SOFTMAX_MAX_L (else S2A_ERR_SIZE); rows >= 0.  Rows up to
+ *                 1024 (every attention of the paper's models) take the tuned
+ *                 kernels; longer rows take one block per row, untuned, with at
+ *                 most 2^31 - 1 rows per call
  * Inputs of -inf (masked logits) give y = 0.  Needs no s2a_qtable_init.
  * x, y (dy, dx) and codes 16-byte aligned take the LDS-staged kernels; any other
  * alignment takes element-wise kernels with the same results.
  */
-#define S2A_SOFTMAX_MAX_L 1024
+#define S2A_SOFTMAX_MAX_L (1 << 20)
 int s2a_softmax_fwd(const void* x, void* y, uint8_t* codes, float* qparams, int64_t rows, int64_t L,
                     int dtype, void* stream);
 int s2a_softmax_bwd(const void* dy, const uint8_t* codes, const float* qparams, void* dx,

@@ -350,6 +350,12 @@ template <bool BF16>
 int launch_softmax_fwd(const void* x, void* y, uint8_t* codes, float* qp, int64_t rows, int L,
                        hipStream_t st)
 {
+    if (L > s2a::kSoftmaxShortL) {
+        if (rows > 0x7fffffffLL) return S2A_ERR_SIZE;
+        return checked_launch([&] {
+            s2a::softmax_fwd_long_kernel<BF16><<<dim3((unsigned)rows), dim3(s2a::kSoftmaxBlock), 0, st>>>(x, y, codes, qp, L);
+        });
+    }
     if (aligned(x, 16) && aligned(y, 16) && aligned(codes, 16))
         switch (softmax_pair_group<BF16>(L)) {
             case 4: return launch_softmax_fwd_staged<BF16, 4>(x, y, codes, qp, rows, L, st);
@@ -373,6 +379,12 @@ template <bool BF16>
 int launch_softmax_bwd(const void* dy, const uint8_t* codes, const float* qp, void* dx,
                        int64_t rows, int L, hipStream_t st)
 {
+    if (L > s2a::kSoftmaxShortL) {
+        if (rows > 0x7fffffffLL) return S2A_ERR_SIZE;
+        return checked_launch([&] {
+            s2a::softmax_bwd_long_kernel<BF16><<<dim3((unsigned)rows), dim3(s2a::kSoftmaxBlock), 0, st>>>(dy, codes, qp, dx, L);
+        });
+    }
     if (aligned(dy, 16) && aligned(dx, 16) && aligned(codes, 16))
         switch (softmax_pair_group<BF16>(L)) {
             case 4: return launch_softmax_bwd_staged<BF16, 4>(dy, codes, qp, dx, rows, L, st);
@@ -467,6 +479,7 @@ int check_lrp(int64_t batch, int64_t N, int64_t C, int r, int dtype)
 }
 
 static_assert(s2a::kQsFloats == S2A_QSTATE_FLOATS, "header and kernels disagree on the qstate size");
+static_assert(s2a::kSoftmaxMaxL == S2A_SOFTMAX_MAX_L, "header and kernels disagree on the longest softmax row");
 
 // Both kernels of the Low-Rank-Prompt backward pass; `work` holds N*C floats (the batch-summed
 // gradient between the two).  Arguments are checked by the callers.

@@ -923,7 +923,8 @@ __global__ __launch_bounds__(kBlock) void relu_bwd_kernel_unaligned(const void* 
 // and 2j+1 sit in neighbouring lanes at the same step, and the even lane packs
 // both codes into the byte it stores.
 constexpr int kSoftmaxSlots = 16;    // elements (fallback kernels) or element pairs (staged kernels) per lane at most
-constexpr int kSoftmaxMaxL = 64 * kSoftmaxSlots;
+constexpr int kSoftmaxShortL = 64 * kSoftmaxSlots;  // rows up to here are held in the registers of one lane group
+constexpr int kSoftmaxMaxL = 1 << 20;               // longer rows: one block per row, several passes (below)
 
 // exp(x - m) for x <= m.  The bf16 storage path takes the plain route.  The
 // fp32 storage path keeps 1e-6 relative accuracy down to the smallest results:
@@ -1450,6 +1451,100 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_kernel(const void* 
             const int idx = l + k * G;
             if (live && idx < L) store_elem<BF16>(dx, row * L + idx, yh[k] * (g[k] - dot));
         }
+}
+
+// ---- rows longer than kSoftmaxShortL: one block per row, the row re-read from the caches ----
+//
+// No attention of the paper's models has such rows (197 .. 577); this path is there so that the
+// entry points hold for any L, and is not tuned.  Forward: pass 1 finds max and min of x, pass 2
+// the sum of the exponentials (fp64 accumulators: a lane adds up to L / 256 terms), pass 3 forms y
+// and the codes pair by pair, so a lane owns whole code bytes.  lo and hi are the images of the
+// extreme x (y is monotone in x), as in the other kernels.  x is only overwritten in pass 3, by
+// the lane that read the element, so y may be x.  Backward: pass 1 the dot product, pass 2 dx.
+
+// Combine one value per wave over the block's waves; every lane gets the result.  `slots` holds
+// one T per wave; two barriers, so it can be used again right away.
+template <typename T, typename F>
+__device__ __forceinline__ T block_combine(T wave_value, T* slots, F f)
+{
+    const int wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
+    if (threadIdx.x % kWave == 0) slots[wave] = wave_value;
+    __syncthreads();
+    T v = slots[0];
+    for (int w = 1; w < waves; ++w) v = f(v, slots[w]);
+    __syncthreads();
+    return v;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kSoftmaxBlock) void softmax_fwd_long_kernel(const void* x, void* y, uint8_t* codes,
+                                                                         float* __restrict__ qparams, int L)
+{
+    __shared__ float fslots[kSoftmaxBlock / kWave];
+    __shared__ double dslots[kSoftmaxBlock / kWave];
+    const int64_t row = blockIdx.x, base = row * L;
+    const int rb = (L + 1) / 2;
+    float m = -__builtin_inff(), xmin = __builtin_inff();
+    for (int idx = threadIdx.x; idx < L; idx += kSoftmaxBlock) {
+        const float v = load_elem<BF16>(x, base + idx);
+        m = vmax(m, v);
+        xmin = vmin(xmin, v);
+    }
+    m = block_combine(group_max<kWave>(m), fslots, [](float a, float b) { return vmax(a, b); });
+    xmin = block_combine(group_min<kWave>(xmin), fslots, [](float a, float b) { return vmin(a, b); });
+    double sum = 0.0;
+    for (int idx = threadIdx.x; idx < L; idx += kSoftmaxBlock)
+        sum += (double)exp_diff<BF16>(load_elem<BF16>(x, base + idx), m);
+    sum = block_combine(group_sum<kWave>(sum), dslots, [](double a, double b) { return a + b; });
+    const float inv = (float)(1.0 / sum);
+    const float hi = exp_diff<BF16>(m, m) * inv;
+    const float lo = exp_diff<BF16>(xmin, m) * inv;
+    const float scale = (hi - lo) / 15.0f;
+    const float inv_scale = scale > 0.0f ? 15.0f / (hi - lo) : 0.0f;
+    if (threadIdx.x == 0) {
+        qparams[2 * row] = lo;
+        qparams[2 * row + 1] = scale;
+    }
+    for (int pair = threadIdx.x; pair < rb; pair += kSoftmaxBlock) {
+        uint32_t byte = 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int idx = 2 * pair + h;
+            if (idx < L) {
+                const float yk = exp_diff<BF16>(load_elem<BF16>(x, base + idx), m) * inv;
+                const float t = __builtin_fmaf(yk - lo, inv_scale, 0.5f);
+                uint32_t c;
+                asm("v_cvt_u32_f32 %0, %1" : "=v"(c) : "v"(t));
+                c = c < 15u ? c : 15u;
+                byte |= c << (4 * h);
+                store_elem<BF16>(y, base + idx, yk);
+            }
+        }
+        codes[row * rb + pair] = (uint8_t)byte;
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kSoftmaxBlock) void softmax_bwd_long_kernel(const void* dy, const uint8_t* codes,
+                                                                         const float* __restrict__ qparams, void* dx,
+                                                                         int L)
+{
+    __shared__ double dslots[kSoftmaxBlock / kWave];
+    const int64_t row = blockIdx.x, base = row * L;
+    const int rb = (L + 1) / 2;
+    const float lo = qparams[2 * row], scale = qparams[2 * row + 1];
+    double acc = 0.0;
+    for (int idx = threadIdx.x; idx < L; idx += kSoftmaxBlock) {
+        const uint32_t byte = codes[row * rb + (idx >> 1)];
+        const float yh = __builtin_fmaf((float)((byte >> (4 * (idx & 1))) & 15u), scale, lo);
+        acc += (double)(yh * load_elem<BF16>(dy, base + idx));
+    }
+    const float dot = (float)block_combine(group_sum<kWave>(acc), dslots, [](double a, double b) { return a + b; });
+    for (int idx = threadIdx.x; idx < L; idx += kSoftmaxBlock) {
+        const uint32_t byte = codes[row * rb + (idx >> 1)];
+        const float yh = __builtin_fmaf((float)((byte >> (4 * (idx & 1))) & 15u), scale, lo);
+        store_elem<BF16>(dx, base + idx, yh * (load_elem<BF16>(dy, base + idx) - dot));
+    }
 }
 
 // --------------------------------------- Channel Average Pooling ----------

@@ -23,7 +23,7 @@ ERR_NOT_INIT = -5
 ERR_LAUNCH = -6
 ERR_ALIGN = -7
 QSTATE_FLOATS = 544
-SOFTMAX_MAX_L = 1024
+SOFTMAX_MAX_L = 1 << 20
 LRP_NOALLOC_MAX_FLOATS = 1 << 20
 
 EXPORTS = ("s2a_qtable_init", "s2a_qtable_get", "s2a_act_fwd", "s2a_act_bwd",

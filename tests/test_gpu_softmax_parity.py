@@ -149,6 +149,25 @@ def test_every_row_length(dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("L", [1025, 1026, 2048, 4097, 20001])
+def test_rows_longer_than_the_register_kernels_hold(dtype, L):
+    """L above 1024: one block per row, the row read three times (forward) or twice (backward).  Buffers
+    aligned and one element off; a few rows, with masked entries in the second case."""
+    for rows, masked, offset in ((1, False, 0), (5, True, 1)):
+        x = _logits(rows, L, dtype, seed=L + rows, scale=3.0, masked=masked)
+        dy = wl.draw_dy(rows * L, 1.0, dtype, seed=L + rows + 1)
+        _run_and_check(x, dy, dtype, rows, L, offset=offset)
+
+
+def test_longest_row():
+    """One row of S2A_SOFTMAX_MAX_L elements."""
+    L = s2a.SOFTMAX_MAX_L
+    x = _logits(1, L, wl.BF16, seed=77, scale=4.0)
+    dy = wl.draw_dy(L, 1.0, wl.BF16, seed=78)
+    _run_and_check(x, dy, wl.BF16, 1, L)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("L", [49, 197, 257])
 def test_masked_and_peaked_rows(dtype, L):
     rows = 333
@@ -197,7 +216,7 @@ def test_unaligned_buffers(dtype):
 def test_argument_errors():
     fake = 0x1000
     assert s2a.softmax_fwd(fake, fake, fake, fake, 4, 0, s2a.F32, check=False) == s2a.ERR_SIZE
-    assert s2a.softmax_fwd(fake, fake, fake, fake, 4, 1025, s2a.F32, check=False) == s2a.ERR_SIZE
+    assert s2a.softmax_fwd(fake, fake, fake, fake, 4, s2a.SOFTMAX_MAX_L + 1, s2a.F32, check=False) == s2a.ERR_SIZE
     assert s2a.softmax_fwd(fake, fake, fake, fake, -1, 8, s2a.F32, check=False) == s2a.ERR_SIZE
     assert s2a.softmax_fwd(fake, fake, fake, fake, 4, 8, 9, check=False) == s2a.ERR_DTYPE
     assert s2a.softmax_fwd(fake, None, fake, fake, 4, 8, s2a.F32, check=False) == s2a.ERR_NULL
