@@ -389,9 +389,14 @@ def softmax_row(torch, row: str, rows: int, L: int, dtype: int, steps: int, warm
             "bwd": row_block(f"s2a::softmax_bwd_staged<{dname(dtype)}>", us["bwd"], nbytes, traffic, row)}
 
 
-def cap_lrp_row(torch, row: str, batch: int, N: int, C: int, steps: int, warmup: int, traffic, note=None):
-    """Channel Average Pooling (r = 8) and Low-Rank Prompt (rank 30) on [batch, N, C] bf16 tokens."""
-    r_cap, rank = 8, 30
+LRP_RANK = 30          # the rank of the Low-Rank Prompt rows; Sec. 4.3 scales it up to 100
+LRP_RANK_SCALED = 100
+
+
+def cap_lrp_row(torch, row: str, batch: int, N: int, C: int, steps: int, warmup: int, traffic, note=None,
+                rank: int = LRP_RANK, lrp_only: bool = False):
+    """Channel Average Pooling (r = 8) and Low-Rank Prompt on [batch, N, C] bf16 tokens."""
+    r_cap = 8
     n = batch * N * C
     x = wl.draw_x(n, "normal", 1.5, wl.BF16, 31)
     dy = wl.draw_dy(n, 1e-2, wl.BF16, 32)
@@ -421,10 +426,13 @@ def cap_lrp_row(torch, row: str, batch: int, N: int, C: int, steps: int, warmup:
               "lrp_bwd": 2 * n + 4 * (2 * N * C + 2 * (N * rank + rank * C))}
     kernels = {"cap_fwd": "s2a::cap_fwd_kernel<bf16, 8>", "cap_bwd": "s2a::cap_bwd_kernel<bf16, 8>",
                "lrp_fwd": "s2a::lrp_fwd_kernel<bf16>", "lrp_bwd": "s2a::lrp_batch_sum_kernel<bf16> + s2a::lrp_grad_ab_kernel"}
+    if lrp_only:
+        ops = {k: v for k, v in ops.items() if k.startswith("lrp")}
     us = time_ops(torch, ops, sets, steps, warmup)
     del bufs
     torch.cuda.empty_cache()
-    out = {"shape": f"[{batch}, {N}, {C}] bf16, CAP r={r_cap}, LRP rank {rank}", "buffer_sets": sets}
+    out = {"shape": f"[{batch}, {N}, {C}] bf16, " + ("" if lrp_only else f"CAP r={r_cap}, ") + f"LRP rank {rank}",
+           "buffer_sets": sets}
     for k in ops:
         out[k] = row_block(kernels[k], us[k], nbytes[k], traffic, row, note)
     return out
@@ -568,8 +576,9 @@ def probe(torch, workload: str, reps: int, extras: bool):
         torch.cuda.synchronize()
         del sm
         torch.cuda.empty_cache()
-    for batch, N, C in TOKEN_SHAPES.values():
-        rank, r_cap = 30, 8
+    for (batch, N, C), rank, lrp_only in [(v, LRP_RANK, False) for v in TOKEN_SHAPES.values()] + \
+                                         [(TOKEN_SHAPES["vit_l16_tokens"], LRP_RANK_SCALED, True)]:
+        r_cap = 8
         m = batch * N * C
         tok = wl.draw_x(m, "normal", 1.5, wl.BF16, seed=13)
         A = torch.randn(N, rank, device="cuda") * 0.1
@@ -584,10 +593,12 @@ def probe(torch, workload: str, reps: int, extras: bool):
             s[2].copy_(s[0])
         torch.cuda.synchronize()
         for tt, ty, tfull, dA, dB, work in cl:
-            s2a.cap_fwd(tt.data_ptr(), ty.data_ptr(), m // r_cap, r_cap, wl.BF16, st)
+            if not lrp_only:
+                s2a.cap_fwd(tt.data_ptr(), ty.data_ptr(), m // r_cap, r_cap, wl.BF16, st)
         torch.cuda.synchronize()
         for tt, ty, tfull, dA, dB, work in cl:
-            s2a.cap_bwd(ty.data_ptr(), tfull.data_ptr(), m // r_cap, r_cap, wl.BF16, st)
+            if not lrp_only:
+                s2a.cap_bwd(ty.data_ptr(), tfull.data_ptr(), m // r_cap, r_cap, wl.BF16, st)
         torch.cuda.synchronize()
         for tt, ty, tfull, dA, dB, work in cl:
             s2a.lrp_fwd(tt.data_ptr(), tfull.data_ptr(), A.data_ptr(), B.data_ptr(), batch, N, C, rank, wl.BF16, st)
@@ -599,7 +610,8 @@ def probe(torch, workload: str, reps: int, extras: bool):
         del cl
         torch.cuda.empty_cache()
     print("probe extras: softmax " + ", ".join(f"{k}=[{r},{L}]" for k, (r, L) in SOFTMAX_SHAPES.items())
-          + "; cap/lrp " + ", ".join(f"{k}=[{b},{N},{C}]" for k, (b, N, C) in TOKEN_SHAPES.items()))
+          + "; cap/lrp " + ", ".join(f"{k}=[{b},{N},{C}]" for k, (b, N, C) in TOKEN_SHAPES.items())
+          + f"; lrp rank {LRP_RANK_SCALED} at vit_l16_tokens")
 
 
 # attention-shaped softmax rows: (rows, L).  ViT-B/16 and ViT-L/16: 197 tokens, 12 / 16 heads, batch 64;
@@ -726,6 +738,9 @@ def main():
         for key, (b, N, C) in TOKEN_SHAPES.items():
             note = "launch- and fill/drain-bound at this size" if key == "vit_b16_tokens" else None
             cl[key] = cap_lrp_row(torch, key, b, N, C, sub, 5, traffic, note)
+        key = "vit_l16_tokens"
+        cl[f"{key}_rank_{LRP_RANK_SCALED}"] = cap_lrp_row(torch, f"{key}_rank_{LRP_RANK_SCALED}", *TOKEN_SHAPES[key], sub, 5, traffic,
+                                                         rank=LRP_RANK_SCALED, lrp_only=True)
         rows["cap_lrp"] = cl
         out["next_rows"] = rows
     if not args.no_cpu_baseline:

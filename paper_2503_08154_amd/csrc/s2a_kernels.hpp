@@ -1759,12 +1759,19 @@ __global__ __launch_bounds__(kLrpFwdBlock) void lrp_fwd_kernel(const u32x4* x, u
         const float* Ai = A + (int64_t)i * r;
         const float* Bc = B + c0;
         const bool b_vectors = ((uintptr_t)B & 15u) == 0;  // C and c0 are multiples of EPV, so rows follow B
-        constexpr int KU = 8;  // rows of B this group has in flight at a time: 64 ranks per round over the groups
-        // ROUNDS is fixed at compile time (1 for the paper's ranks up to 64): a run-time loop made
-        // the first loads of x wait at its back edge (forward 9.3 -> 13.6 us at ViT-B/16)
+        // Rows of B this group has in flight at a time, and how many such stages it takes.  Ranks up
+        // to 64 (ROUNDS = 1, the paper's own): 8 rows, one stage.  Above: 4 rows per stage and four
+        // stages, each behind the arithmetic of the one before (its addresses are made to depend on
+        // that result) -- all 16 rows at once, or 8 and 8, need more registers than a 1024-lane block
+        // has, and the compiler spills to memory.  The stage count is fixed at compile time: a
+        // run-time loop made the first loads of x wait at its back edge (forward 9.3 -> 13.6 us at
+        // ViT-B/16).
+        constexpr int KU = ROUNDS == 1 ? 8 : 4, STAGES = ROUNDS * 8 / KU;
 #pragma unroll
-        for (int round = 0; round < ROUNDS; ++round) {
-            const int k0 = round * KU * kLrpGroups;
+        for (int stage = 0; stage < STAGES; ++stage) {
+            int k_bias = 0;
+            if (stage > 0) asm volatile("" : "+v"(k_bias) : "v"(p[0]));
+            const int k0 = stage * KU * kLrpGroups + k_bias;
             float a[KU];
             u32x4 bk[KU][EPV / 4];
 #pragma unroll
