@@ -288,6 +288,20 @@ __device__ __forceinline__ float vmin(float a, float b)
     return r;
 }
 
+// Three-operand maximum / minimum: one VALU op takes in both elements of a pair.
+__device__ __forceinline__ float vmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float vmin3(float a, float b, float c)
+{
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // All-reduce over the G lanes of a row group; F(a, b) is the (commutative) combiner.
 template <int G, typename T, typename F>
 __device__ __forceinline__ T group_reduce(T v, F f)
@@ -399,17 +413,14 @@ __device__ __forceinline__ uint32_t fwd_vector(u32x4& v, Bin bin)
 // address cost 48 us on MI355X (device-scope atomics serialise at about 12 ns
 // each), three times the range pass itself; partials also need no reset
 // launch and make the result independent of the order blocks finish in.
-constexpr int kRangeBlocks = 256, kRangeBlock = 1024;
+// Lanes per block by measurement at the ViT-L shape (range pass + forward kernel, 1024 / 512 / 256
+// lanes): 38.8 / 38.2 / 37.9 us for activations that reach both clip limits (every wave stops after
+// its first loads, so fewer lanes read less), 55.6 / 55.3 / 56.3 us for a tensor that stays inside.
+constexpr int kRangeBlocks = 256, kRangeBlock = 512;
 constexpr int kQsMin = 2, kQsScale = 3, kQsInv = 4, kQsOff = 5, kQsTable = 16, kQsPartMin = 32,
               kQsPartMax = 32 + kRangeBlocks, kQsFloats = 32 + 2 * kRangeBlocks;
 
 // --------------------------------------------- measured range (Eq. 8) -----
-
-// clip(x, -2, 2) with NaN -> -2 (a value below the range), as in the forward binning.
-__device__ __forceinline__ float clip_for_range(float x)
-{
-    return (x != x) ? -2.0f : __builtin_amdgcn_fmed3f(x, -2.0f, 2.0f);
-}
 
 // Block-wide minimum and maximum (all lanes call; lane 0 of the block gets the result).
 template <int BLOCK>
@@ -437,16 +448,17 @@ __device__ __forceinline__ void block_minmax(float& lo, float& hi)
 
 // Some lane of the wave has met the lower clip limit and some lane the upper one: nothing the
 // wave could still read changes min = -2, max = 2.  Uniform over the active lanes.
-__device__ __forceinline__ bool wave_saturated(float lo, float hi)
+// (lo and hi are the unclipped extremes; a NaN counts as -2.)
+__device__ __forceinline__ bool wave_saturated(float lo, float hi, bool nan)
 {
-    return __builtin_amdgcn_ballot_w64(lo == -2.0f) != 0 && __builtin_amdgcn_ballot_w64(hi == 2.0f) != 0;
+    return __builtin_amdgcn_ballot_w64(lo <= -2.0f || nan) != 0 && __builtin_amdgcn_ballot_w64(hi >= 2.0f) != 0;
 }
 
 // Pass 1 of the measured range: per-block min / max of clip(x).  Each block
 // walks its own contiguous share of the 16-byte vectors (of the elements when
-// ALIGNED is false) with two predicated loads in flight per lane, and leaves
-// its pair in qs[kQsPartMin + b] and qs[kQsPartMax + b] (+inf / -inf if it saw
-// no element); all kRangeBlocks slots are written whatever the grid size.
+// ALIGNED is false) and leaves its pair in qs[kQsPartMin + b] and
+// qs[kQsPartMax + b] (+inf / -inf if it saw no element); all kRangeBlocks slots
+// are written whatever the grid size.
 // The clip bounds the result: a wave whose first round of loads held an
 // element at or beyond each clip limit stops reading (wave_saturated), so a
 // tensor with values beyond both limits throughout -- the activations of the
@@ -455,18 +467,28 @@ __device__ __forceinline__ bool wave_saturated(float lo, float hi)
 // inside a limit are read to the end, with ordinary cached loads on purpose: a
 // tensor that fits the 256 MB on-die cache is then still there when the
 // forward kernel reads it again (measured: the forward kernel takes 32.3 us
-// instead of 36.1 us at the ViT-L shape).
+// instead of 36.1 us at the ViT-L shape; with streaming loads the two kernels
+// together take the same time, the pass gaining what the forward kernel loses).
+// That full pass runs at 4.4 TB/s (23 us for 103 MB) whatever was tried on it:
+// two or eight loads in flight per lane, 256 .. 1024 lanes per block, a third of
+// the arithmetic, the whole grid sweeping the tensor instead of a share per
+// block, streaming loads -- all within 1 %.
 template <bool BF16, bool ALIGNED>
 __global__ __launch_bounds__(kRangeBlock) void range_minmax_kernel(const void* x, float* qs,
                                                                    int64_t n)
 {
     constexpr int EPV = BF16 ? 8 : 4;
+    // The clip is monotone, so it is applied to the two results instead of to every element; a NaN
+    // (which the clip sends to -2) loses against numbers in v_min3 / v_max3 and is remembered by a
+    // flag.  Two elements cost one min3, one max3 and one unordered compare.
     float lo = __builtin_inff(), hi = -__builtin_inff();
-    auto take1 = [&](float a) {
-        a = clip_for_range(a);
-        lo = fminf(lo, a);
-        hi = fmaxf(hi, a);
+    bool nan = false;
+    auto take2 = [&](float a, float b) {
+        lo = vmin3(lo, a, b);
+        hi = vmax3(hi, a, b);
+        nan |= __builtin_isunordered(a, b);
     };
+    auto take1 = [&](float a) { take2(a, a); };
     int64_t done = 0;
     if (ALIGNED) {
         const int64_t nvec = n / EPV;
@@ -474,43 +496,81 @@ __global__ __launch_bounds__(kRangeBlock) void range_minmax_kernel(const void* x
         const int64_t share = (nvec + gridDim.x - 1) / gridDim.x;
         const int64_t beg = (int64_t)blockIdx.x * share;
         const int64_t end = beg + share < nvec ? beg + share : nvec;
-        constexpr int U = 2;
-        auto take_round = [&](int64_t i) {
-            u32x4 v[U];
-            bool ok[U];
+        // Loads are never predicated: a position past the block's share is replaced by the share's
+        // last vector (a duplicate changes neither extreme), so the code between the loads and their
+        // use is straight-line and the compiler lets them overlap.
+        const int64_t last = end - 1;
+        auto eat = [&](const u32x4& v) {
 #pragma unroll
-            for (int k = 0; k < U; ++k) {
-                ok[k] = i + k * kRangeBlock < end;
-                if (ok[k]) v[k] = xv[i + k * kRangeBlock];
-            }
-#pragma unroll
-            for (int k = 0; k < U; ++k) {
-                if (!ok[k]) continue;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (BF16) {
-                        take1(bf16_lo(v[k][j]));
-                        take1(bf16_hi(v[k][j]));
-                    } else {
-                        take1(as_f32(v[k][j]));
-                    }
+            for (int j = 0; j < 4; j += 2) {
+                if (BF16) {
+                    take2(bf16_lo(v[j]), bf16_hi(v[j]));
+                    take2(bf16_lo(v[j + 1]), bf16_hi(v[j + 1]));
+                } else {
+                    take2(as_f32(v[j]), as_f32(v[j + 1]));
                 }
             }
         };
-        // The question is asked once, after the wave's first round (1024 or 2048 elements): asked
-        // inside the loop it makes every round's loads wait for the data of the round before, which
-        // costs a tensor that never saturates 4 %.
-        int64_t i = beg + threadIdx.x;
-        if (i < end) take_round(i);
-        if (!wave_saturated(lo, hi))
-            for (i += U * kRangeBlock; i < end; i += U * kRangeBlock) take_round(i);
+        if (beg < end) {
+            // first round, two vectors per lane (1024 or 2048 elements per wave); then the question
+            // whether the wave can stop is asked once: asked in every round it makes each round's
+            // loads wait for the data of the round before
+            constexpr int U0 = 2;
+            {
+                u32x4 v[U0];
+#pragma unroll
+                for (int k = 0; k < U0; ++k) {
+                    const int64_t at = beg + threadIdx.x + k * kRangeBlock;
+                    v[k] = xv[at < end ? at : last];
+                }
+#pragma unroll
+                for (int k = 0; k < U0; ++k) eat(v[k]);
+            }
+            // the rest of the share (tensors that stay inside a clip limit), four vectors per lane
+            // and round, the next round's loads requested before this round's are used: two buffers
+            // that swap roles, so that no loaded value is copied (a copy would wait for it)
+            constexpr int U = 4;
+            constexpr int64_t STEP = (int64_t)U * kRangeBlock;
+            auto fetch = [&](u32x4(&v)[U], int64_t base) {
+#pragma unroll
+                for (int k = 0; k < U; ++k) {
+                    const int64_t at = base + threadIdx.x + k * kRangeBlock;
+                    v[k] = xv[at < end ? at : last];
+                }
+            };
+            int64_t at = beg + U0 * kRangeBlock;  // uniform over the block
+            if (at < end && !wave_saturated(lo, hi, nan)) {
+                u32x4 a[U], b[U];
+                fetch(a, at);
+                for (;;) {
+                    fetch(b, at + STEP);
+#pragma unroll
+                    for (int k = 0; k < U; ++k) eat(a[k]);
+                    at += STEP;
+                    if (at >= end) break;
+                    fetch(a, at + STEP);
+#pragma unroll
+                    for (int k = 0; k < U; ++k) eat(b[k]);
+                    at += STEP;
+                    if (at >= end) break;
+                }
+            }
+        }
         done = nvec * EPV;
     }
     // leftover (or, unaligned, all) elements one by one, spread over the whole grid
     for (int64_t i = done + (int64_t)blockIdx.x * kRangeBlock + threadIdx.x; i < n;
          i += (int64_t)gridDim.x * kRangeBlock) {
-        if (wave_saturated(lo, hi)) break;
+        if (wave_saturated(lo, hi, nan)) break;
         take1(load_elem<BF16>(x, i));
+    }
+    if (nan) {
+        lo = fminf(lo, -2.0f);
+        hi = fmaxf(hi, -2.0f);
+    }
+    if (lo <= hi) {  // the lane has seen an element (otherwise +inf / -inf stay: "no element")
+        lo = __builtin_amdgcn_fmed3f(lo, -2.0f, 2.0f);
+        hi = __builtin_amdgcn_fmed3f(hi, -2.0f, 2.0f);
     }
     block_minmax<kRangeBlock>(lo, hi);
     if (threadIdx.x == 0) {
@@ -1115,20 +1175,6 @@ template <bool BF16>
 __device__ __forceinline__ void lds_out(unsigned char* p, float v)
 {
     if (BF16) *(uint16_t*)p = (uint16_t)pack_bf16(v, 0.0f); else *(float*)p = v;
-}
-
-// Three-operand maximum / minimum: one VALU op takes in both elements of a pair.
-__device__ __forceinline__ float vmax3(float a, float b, float c)
-{
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
-__device__ __forceinline__ float vmin3(float a, float b, float c)
-{
-    float r;
-    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
 }
 
 // exp(x - m) for all elements of one row.  bf16 storage: exp2(x*log2e - m*log2e)
