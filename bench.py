@@ -110,10 +110,12 @@ def build_layers(torch, w: wl.Workload, distinct_seeds: bool):
 
 FWD = {"gelu": lambda L, st: s2a.act_fwd(L.p[0], L.p[1], L.p[2], L.n, L.dtype, st),
        "gelu_dyn": lambda L, st: s2a.act_fwd_dyn(L.p[0], L.p[1], L.p[2], L.p[5], L.n, L.dtype, st),
+       "gelu_in_place": lambda L, st: s2a.act_fwd(L.p[0], L.p[0], L.p[2], L.n, L.dtype, st),
        "silu": lambda L, st: s2a.silu_fwd(L.p[0], L.p[1], L.p[2], L.n, L.dtype, st),
        "relu": lambda L, st: s2a.relu_fwd(L.p[0], L.p[1], L.p[2], L.n, L.dtype, st)}
 BWD = {"gelu": lambda L, st: s2a.act_bwd(L.p[3], L.p[2], L.p[4], L.n, L.dtype, st),
        "gelu_dyn": lambda L, st: s2a.act_bwd_dyn(L.p[3], L.p[2], L.p[5], L.p[4], L.n, L.dtype, st),
+       "gelu_in_place": lambda L, st: s2a.act_bwd(L.p[3], L.p[2], L.p[3], L.n, L.dtype, st),
        "silu": lambda L, st: s2a.silu_bwd(L.p[3], L.p[2], L.p[4], L.n, L.dtype, st),
        "relu": lambda L, st: s2a.relu_bwd(L.p[3], L.p[2], L.p[4], L.n, L.dtype, st)}
 
@@ -452,6 +454,7 @@ def variant_row(torch, name: str, variant: str, steps: int, warmup: int, traffic
     bwd_bytes = (2 * e + side) * n1
     dt = dname(tw.dtype)
     kn = {"gelu_dyn": (f"s2a::range_minmax_kernel<{dt}> + s2a::fwd_dyn_kernel<{dt}>", f"s2a::bwd_kernel<{dt}, dyn>"),
+          "gelu_in_place": (f"s2a::fwd_kernel<{dt}>", f"s2a::bwd_kernel<{dt}>"),
           "silu": (f"s2a::fwd_kernel<{dt}, silu>", f"s2a::bwd_kernel<{dt}>"),
           "relu": (f"s2a::relu_fwd_kernel<{dt}>", f"s2a::relu_bwd_kernel<{dt}>")}[variant]
     return {"workload": name, "buffer_sets": tw.layers,
@@ -725,6 +728,9 @@ def main():
                                                           bytes_per_elem_fwd=3 * e + 0.5, w_override=narrow,
                                                           row_key="vit_l16:gelu_dyn_narrow")
         rows["measured_range_vit_g14_f32"] = variant_row(torch, "vit_g14_f32", "gelu_dyn", sub, subw, traffic)
+        # y written over x and dx over dy (the entry points allow exact aliasing): the same bytes, the
+        # read and the write stream on the same DRAM pages.  Timing only: the values decay over the steps.
+        rows["in_place_vit_l16"] = variant_row(torch, "vit_l16", "gelu_in_place", sub, subw, traffic)
         rows["silu"] = variant_row(torch, "vit_l16", "silu", sub, subw, traffic)
         rows["relu_mask_vit_l16"] = variant_row(torch, "vit_l16", "relu", sub, subw, traffic)
         rows["relu_mask_vit_g14_f32"] = variant_row(torch, "vit_g14_f32", "relu", sub, subw, traffic)
