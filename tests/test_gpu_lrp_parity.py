@@ -82,7 +82,9 @@ def _check(batch, N, C, r, dtype, seed, inplace=False, b_offset=0, out_offset=0)
 
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("shape", [(1, 1, 8, 1), (2, 3, 16, 5), (3, 7, 24, 30), (5, 197, 768, 30), (64, 17, 256, 64),
-                                   (1, 300, 1024, 2), (9, 50, 40, 30)])
+                                   (1, 300, 1024, 2), (9, 50, 40, 30),
+                                   # the 16 x 16 tiles of the backward products: exact, one past, rank limit on one token
+                                   (2, 16, 64, 16), (2, 17, 72, 17), (1, 33, 136, 33), (1, 1, 8, 128), (3, 1, 1032, 1)])
 def test_shapes(dtype, shape):
     batch, N, C, r = shape
     _check(batch, N, C, r, dtype, seed=sum(shape))
